@@ -1,0 +1,197 @@
+"""Pins for the oracle's k-hop and layer (collective) sampling."""
+import numpy as np
+import pytest
+from scipy import stats
+
+import oracle
+from paper_2009_06693_amd import inputs
+
+
+def _og(g):
+    return oracle.OracleGraph(g.row_offsets, g.col_indices, g.weights)
+
+
+def test_khop_with_unit_fanouts_is_a_uniform_walk():
+    g = inputs.small_graph(8, 1500, seed=3)
+    og = _og(g)
+    roots = np.arange(g.V, dtype=np.int32)
+    walk = oracle.deepwalk(og, roots, 6, seed=42)
+    hops = oracle.khop(og, roots, [1] * 6, seed=42)
+    for i in range(6):
+        assert hops[i].shape == (g.V, 1)
+        assert (hops[i][:, 0] == walk[i]).all()
+
+
+def test_khop_shapes_parents_and_nulls():
+    # 0 -> {1,2}; 1 -> {0}; 2 has no out-edges; 3 isolated
+    g = inputs.from_edges(4, [(0, 1), (0, 2), (1, 0)])
+    og = _og(g)
+    out = oracle.khop(og, [0, 3, 1], [4, 3], seed=6)
+    assert out[0].shape == (3, 4) and out[1].shape == (3, 12)
+    assert set(out[0][0].tolist()) <= {1, 2}
+    assert (out[0][1] == -1).all() and (out[1][1] == -1).all()   # isolated root
+    assert (out[0][2] == 0).all()
+    for s in range(3):
+        for j in range(12):
+            parent = out[0][s, j // 3]
+            child = out[1][s, j]
+            if parent in (-1, 2):
+                assert child == -1                                   # children of NULL / dead end
+            elif parent == 1:
+                assert child == 0
+            else:
+                assert child in (1, 2)
+
+
+def test_khop_single_step_is_one_hop_sampling():
+    # one step of fanout m: m independent uniform neighbours of the root (MVS-style 1-hop)
+    d, m, S = 5, 8, 30000
+    g = inputs.from_edges(d + 1, [(0, i + 1) for i in range(d)])
+    out = oracle.khop(_og(g), np.zeros(S, dtype=np.int32), [m], seed=10)[0]
+    for j in range(m):
+        counts = np.bincount(out[:, j], minlength=d + 1)[1:]
+        assert stats.chisquare(counts).pvalue > 1e-4
+    # slots of one sample are independent draws: joint of slots 0 and 1 is uniform on d*d
+    joint = np.bincount((out[:, 0] - 1) * d + (out[:, 1] - 1), minlength=d * d)
+    assert stats.chisquare(joint).pvalue > 1e-4
+
+
+def test_khop_second_hop_marginals():
+    und = [(0, 1), (0, 2), (0, 3), (1, 2), (2, 3), (3, 4), (4, 5), (1, 5), (2, 5)]
+    g = inputs.from_edges(6, und + [(v, u) for u, v in und])
+    og = _og(g)
+    S = 20000
+    out = oracle.khop(og, np.zeros(S, dtype=np.int32), [3, 4], seed=2)
+    off = g.row_offsets
+    parents = np.repeat(out[0], 4, axis=1)        # parent of slot j is slot j // 4
+    for v in range(6):
+        sel = out[1][parents == v]
+        if sel.size == 0:
+            continue
+        nbrs = g.col_indices[off[v]:off[v + 1]]
+        counts = np.array([(sel == u).sum() for u in nbrs])
+        assert counts.sum() == sel.size
+        assert stats.chisquare(counts).pvalue > 1e-4
+
+
+def test_khop_counter_uses_the_slot_within_the_sample():
+    g = inputs.small_graph(8, 1500, seed=3)
+    og = _og(g)
+    hub = int(np.argmax(g.degrees()))
+    roots = np.array([hub, 9, hub], dtype=np.int32)
+    out = oracle.khop(og, roots, [6, 2], seed=8)
+    # same root, different sample id: different draws
+    assert (out[0][0] != out[0][2]).any()
+    # sample_id_base shifts the slice
+    part = oracle.khop(og, roots[1:], [6, 2], seed=8, sample_id_base=1)
+    assert (part[0] == out[0][1:]).all() and (part[1] == out[1][1:]).all()
+    # draws follow the generator: slot j of step 0 of sample 0
+    off = g.row_offsets
+    d = int(off[hub + 1] - off[hub])
+    for j in range(6):
+        r0 = int(oracle.draw(8, 0, j, 0)[0])
+        assert out[0][0, j] == g.col_indices[off[hub] + (r0 * d >> 32)]
+
+
+# ----------------------------------------------------------------------------- layer
+
+def _layer_graph():
+    # degrees: 0:3, 1:2, 2:4, 3:1, 4:2, 5:0 (directed entries)
+    edges = [(0, 1), (0, 2), (0, 4), (1, 2), (1, 3), (2, 0), (2, 1), (2, 3), (2, 5), (3, 4),
+             (4, 0), (4, 5)]
+    return inputs.from_edges(6, edges)
+
+
+def _layer_expected(g, transits):
+    """P(u) proportional to the sum over transit rows v containing u of floor(2^48/deg(v)^2)."""
+    off = g.row_offsets
+    mass = np.zeros(g.V)
+    for v in transits:
+        if v < 0:
+            continue
+        d = int(off[v + 1] - off[v])
+        if d == 0:
+            continue
+        c = (1 << 48) // (d * d)
+        for u in g.col_indices[off[v]:off[v + 1]]:
+            mass[u] += c
+    return mass / mass.sum()
+
+
+def test_layer_brute_force_distribution():
+    g = _layer_graph()
+    og = _og(g)
+    rps, m, B = 4, 50, 4000
+    batch = np.array([0, 2, 3, 0], dtype=np.int32)         # repeated transit keeps both copies
+    roots = np.tile(batch, B)
+    out = oracle.layer(og, roots, rps, [m], seed=12)[0]
+    assert out.shape == (B, m)
+    prob = _layer_expected(g, batch)
+    counts = np.bincount(out.reshape(-1), minlength=g.V)
+    assert (counts[prob == 0] == 0).all()
+    keep = prob > 0
+    assert stats.chisquare(counts[keep], prob[keep] * counts.sum()).pvalue > 1e-4
+    # hand check of the weights: deg 3 -> c = 2^48/9, deg 4 -> 2^48/16, deg 1 -> 2^48
+    c3, c4, c1 = (1 << 48) // 9, (1 << 48) // 16, 1 << 48
+    mass = np.zeros(6)
+    mass[[1, 2, 4]] += 2 * c3
+    mass[[0, 1, 3, 5]] += c4
+    mass[4] += c1
+    assert np.allclose(prob, mass / mass.sum())
+
+
+def test_layer_second_step_uses_previous_layer_as_transits():
+    g = _layer_graph()
+    og = _og(g)
+    B = 6000
+    roots = np.tile(np.array([3], dtype=np.int32), B)      # 3 -> {4}: the first layer is all 4s
+    out = oracle.layer(og, roots, 1, [2, 40], seed=1)
+    assert (out[0] == 4).all()
+    prob = _layer_expected(g, [4, 4])
+    counts = np.bincount(out[1].reshape(-1), minlength=g.V)
+    keep = prob > 0
+    assert (counts[~keep] == 0).all()
+    assert stats.chisquare(counts[keep], prob[keep] * counts.sum()).pvalue > 1e-4
+
+
+def test_layer_single_transit_is_uniform_over_its_list():
+    g = _layer_graph()
+    out = oracle.layer(_og(g), np.full(5000, 2, dtype=np.int32), 1, [16], seed=3)[0]
+    counts = np.bincount(out.reshape(-1), minlength=6)
+    assert counts[[2, 4]].sum() == 0
+    assert stats.chisquare(counts[[0, 1, 3, 5]]).pvalue > 1e-4
+
+
+def test_layer_equal_degrees_give_uniform_over_the_concatenation():
+    # 0 -> {2,3}, 1 -> {3,4}: both degree 2, so 3 is twice as likely as 2 or 4
+    g = inputs.from_edges(5, [(0, 2), (0, 3), (1, 3), (1, 4)])
+    out = oracle.layer(_og(g), np.tile(np.array([0, 1], dtype=np.int32), 4000), 2, [10], seed=4)[0]
+    counts = np.bincount(out.reshape(-1), minlength=5)[2:]
+    assert stats.chisquare(counts, np.array([0.25, 0.5, 0.25]) * counts.sum()).pvalue > 1e-4
+
+
+def test_layer_exact_index_arithmetic():
+    # One transit of degree 3: total = 3*c, x = floor(r64*total/2^64), index = x // c.
+    g = inputs.from_edges(4, [(0, 1), (0, 2), (0, 3)])
+    out = oracle.layer(_og(g), np.zeros(50, dtype=np.int32), 1, [7], seed=77)[0]
+    c = (1 << 48) // 9
+    for b in range(50):
+        for j in range(7):
+            r = oracle.draw(77, b, j, 0)
+            x = ((int(r[0]) << 32 | int(r[1])) * (3 * c)) >> 64
+            assert out[b, j] == 1 + x // c
+
+
+def test_layer_all_dead_transits_give_null():
+    g = _layer_graph()
+    out = oracle.layer(_og(g), np.array([5, -1, 5, 5], dtype=np.int32), 2, [3, 3], seed=1)
+    assert (out[0] == -1).all() and (out[1] == -1).all()
+
+
+def test_layer_sample_id_base():
+    g = inputs.small_graph(8, 1500, seed=3)
+    og = _og(g)
+    roots = inputs.permutation(g.V, 5)[:8 * 16]
+    full = oracle.layer(og, roots, 16, [32, 32], seed=5)
+    part = oracle.layer(og, roots[3 * 16:6 * 16], 16, [32, 32], seed=5, sample_id_base=3)
+    assert (full[0][3:6] == part[0]).all() and (full[1][3:6] == part[1]).all()
