@@ -1,0 +1,233 @@
+/*
+ * nd.h - C ABI of the transit-parallel graph sampling library for one AMD
+ * MI355X (gfx950).
+ *
+ * The calls follow the problem statement of the NextDoor paper (Section 3 and
+ * Section 4.1): the inputs are a graph, an initial set of samples (roots), and
+ * a sampling application with its parameters; the output is the expanded
+ * samples, one int32 array per step, resident in device memory (Section 4.1,
+ * "Output format", the per-step form).  Every step is executed transit-
+ * parallel (Section 5.2 and Section 6): the (transit, sample-slot) pairs of the
+ * step are grouped by transit vertex with a radix sort and a segmented scan,
+ * the transits are split into three scheduling classes by the number of
+ * neighbours they must produce (Section 6.1.2, Table "Types of kernels"), and
+ * one kernel per class draws the neighbours.
+ *
+ * Conventions
+ *   - All functions return 0 on success or a negative nd_status code; the
+ *     message of the last failure on the calling thread is nd_last_error().
+ *     No exception crosses this boundary and no argument is a C++ or torch
+ *     type.
+ *   - "host" / "device" after a pointer says where the memory must live.
+ *   - The NULL vertex is -1 (ND_NULL_VERTEX).  A sample slot whose transit is
+ *     NULL, or has no out-edges, receives NULL at this and all later steps
+ *     (Section 4.1: `next` may return NULL; a walk without transits has ended).
+ *   - Random numbers: Philox4x32-10 with key = (seed low word, seed high word)
+ *     and counter = (sample_id_base + sample index, slot within the sample,
+ *     step, attempt).  The output therefore depends only on (graph, app,
+ *     params, roots, seed) and never on how samples are grouped, scheduled or
+ *     split over calls.
+ */
+#ifndef ND_H_
+#define ND_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ND_VERSION 100
+#define ND_NULL_VERTEX (-1)
+#define ND_MAX_FANOUT_STEPS 8 /* k-hop / layer steps */
+#define ND_MAX_WALK_STEPS 4096
+#define ND_MAX_LAYER_TRANSITS 4096 /* roots_per_sample and layer fanouts */
+
+typedef enum nd_status {
+    ND_OK = 0,
+    ND_ERR_NULL_POINTER = -1,
+    ND_ERR_BAD_ARGUMENT = -2,  /* sizes, enum values, parameter ranges */
+    ND_ERR_BAD_GRAPH = -3,     /* CSR fails validation (see nd_graph_create) */
+    ND_ERR_BAD_WEIGHT = -4,    /* weight not finite, <= 0 or >= 2^15, or a row total >= 2^39 */
+    ND_ERR_NO_WEIGHTS = -5,    /* use_weights on a graph created without weights */
+    ND_ERR_WORKSPACE = -6,     /* workspace too small or misaligned */
+    ND_ERR_HIP = -7,           /* a HIP runtime call failed */
+    ND_ERR_BAD_ROOT = -8,      /* reported by nd_sample_status: a root outside [0, V) */
+    ND_ERR_TOO_LARGE = -9      /* V >= 2^31, too many samples or slots for 32-bit ids */
+} nd_status;
+
+/* Sampling applications (Section 3 and Section 4.2 of the paper). */
+typedef enum nd_app {
+    ND_DEEPWALK = 0, /* fixed-length static walk, uniform or weight-proportional      */
+    ND_PPR = 1,      /* static walk that ends with probability term_prob per step     */
+    ND_NODE2VEC = 2, /* second-order walk, rejection sampling with bias p, q          */
+    ND_KHOP = 3,     /* GraphSAGE k-hop: fanout[i] uniform neighbours per transit     */
+    ND_LAYER = 4     /* collective: fanout[i] draws from the transits' combined       */
+                     /* neighbourhood, LADIES-style weights                           */
+} nd_app;
+
+/* Execution strategy.  Both give identical outputs. */
+typedef enum nd_mode {
+    ND_MODE_TRANSIT_PARALLEL = 0, /* the paper's method (Section 5.2, Section 6)     */
+    ND_MODE_SAMPLE_PARALLEL = 1   /* one lane per (sample, slot), no grouping          */
+                                  /* (Section 5.1), kept as the ablation baseline     */
+} nd_mode;
+
+/* Scheduling classes (Section 6.1.2), re-derived for 64-lane wavefronts. */
+typedef enum nd_sched_class {
+    ND_CLASS_AUTO = -1,
+    ND_CLASS_SUBWAVE = 0,   /* several transits share one wavefront                   */
+    ND_CLASS_WORKGROUP = 1, /* one workgroup per transit, adjacency list in LDS       */
+    ND_CLASS_GRID = 2       /* one transit spread over many workgroups                */
+} nd_sched_class;
+
+typedef struct nd_params {
+    uint32_t struct_size;      /* sizeof(nd_params), set by nd_params_init             */
+    int32_t num_steps;         /* walks: walk length (PPR: the cap that replaces the   */
+                               /* paper's unbounded step count); k-hop, layer: number  */
+                               /* of entries used in fanout[]                          */
+    int32_t fanout[ND_MAX_FANOUT_STEPS]; /* k-hop: neighbours per transit; layer:     */
+                               /* vertices per sample, at each step                    */
+    int32_t use_weights;       /* walks: draw proportionally to the edge weight        */
+    int32_t bias_convention;   /* node2vec: 0 = return 1/p, common neighbour 1,        */
+                               /* farther 1/q (the node2vec definition); 1 = p, 1/q, 1 */
+                               /* (the wording of Section 4.2)                         */
+    double p, q;               /* node2vec hyper-parameters                            */
+    double term_prob;          /* PPR: probability of ending the walk at each step     */
+    int32_t roots_per_sample;  /* layer: roots that form one sample (batch)            */
+    int32_t n2v_max_attempts;  /* node2vec: rejection attempts before the exact        */
+                               /* fallback draw; part of the output's definition       */
+    uint64_t sample_id_base;   /* id of this call's first sample in the random-number  */
+                               /* counter: a call on roots[a:b] with base a reproduces */
+                               /* that slice of the call on all roots                  */
+    int32_t mode;              /* nd_mode                                              */
+    int32_t sched_force_class; /* nd_sched_class; anything but AUTO is for tests       */
+    int32_t sched_sub_max;     /* largest draw count handled sub-wavefront (0: 64)     */
+    int32_t sched_wg_max;      /* largest draw count handled by one workgroup; also    */
+                               /* the chunk a grid-class transit is cut into (0: 8192) */
+    int32_t lds_stage_policy;  /* 0: stage the adjacency list in LDS when it fits and  */
+                               /* pays; 1: never stage; 2: stage whenever it fits      */
+    int32_t reserved[5];
+} nd_params;
+
+typedef struct nd_graph nd_graph; /* opaque; owned by the library */
+
+/* Fills *p with the defaults (n2v_max_attempts = 64, p = q = 1, mode =
+ * transit-parallel, class AUTO, everything else 0). */
+void nd_params_init(nd_params* p);
+
+/*
+ * Copies a CSR graph into device memory owned by the library (Section 5.1:
+ * the graph lives in GPU global memory) and, when weights are given, builds
+ * what the paper's Vertex class offers (Section 4.1): per vertex the largest
+ * edge weight and the running sums of its edge weights.  Weights are
+ * quantised once to integers, w_q = floor(w * 2^16 + 0.5), and all later
+ * arithmetic on them is integer.
+ *
+ *   row_offsets      V+1 entries, int32 (offsets_are_int64 = 0) or int64; host or device
+ *   col_indices      E entries, int32; every row strictly ascending (no duplicates)
+ *   weights_or_null  E float32 entries or NULL
+ *   src_is_device    0: the three arrays are host memory; 1: device memory
+ *   hip_stream       hipStream_t to work on (NULL = the default stream); the call
+ *                    returns after the work on it has completed
+ *
+ * Errors: ND_ERR_NULL_POINTER; ND_ERR_TOO_LARGE (V >= 2^31 or V < 1 ...);
+ * ND_ERR_BAD_GRAPH (offsets[0] != 0, offsets not monotone, offsets[V] != E, a
+ * column outside [0, V), a row not strictly ascending); ND_ERR_BAD_WEIGHT;
+ * ND_ERR_HIP.  On error *out is NULL and nothing stays allocated.
+ */
+int nd_graph_create(nd_graph** out, int64_t V, int64_t E, const void* row_offsets,
+                    int offsets_are_int64, const int32_t* col_indices,
+                    const float* weights_or_null, int src_is_device, void* hip_stream);
+
+/* Frees the device copy.  Accepts NULL. */
+int nd_graph_destroy(nd_graph* g);
+
+/* V, E, whether weights are present, and the width of the stored offsets. */
+int nd_graph_info(const nd_graph* g, int64_t* V, int64_t* E, int* has_weights,
+                  int* offsets_are_int64);
+
+/*
+ * Sizes of one nd_sample call.
+ *   num_roots        walks and k-hop: one sample per root; layer: a multiple of
+ *                    roots_per_sample (one sample per group of roots)
+ *   num_steps        out: number of per-step output arrays
+ *   step_len         out, host, at least num_steps entries (ND_MAX_WALK_STEPS is
+ *                    always enough): int32 elements of each step's array.
+ *                    Walks: S.  k-hop: S * fanout[0] * ... * fanout[i].
+ *                    Layer: num_samples * fanout[i].
+ *   workspace_bytes  out: device scratch nd_sample needs for these arguments
+ */
+int nd_sample_query(const nd_graph* g, int app, const nd_params* params, int64_t num_roots,
+                    int32_t* num_steps, int64_t* step_len, size_t* workspace_bytes);
+
+/*
+ * Runs every step of the application for all roots, asynchronously on
+ * hip_stream, allocating nothing.
+ *
+ *   roots_dev        device, num_roots int32 vertices.  A root outside [0, V) is
+ *                    treated as NULL and recorded (see nd_sample_status).
+ *   seed             Philox key
+ *   step_out_dev     host array of num_steps device pointers, caller-allocated,
+ *                    step i holding step_len[i] int32.  Layouts:
+ *                      walks   out[i][s]             vertex walk s adds at step i
+ *                      k-hop   out[i][s*W_i + j]     slot j of sample s; its parent
+ *                                                    is slot j / fanout[i] of step i-1
+ *                      layer   out[i][b*fanout[i]+j] j-th vertex of sample b's layer i
+ *                    Roots are not repeated in the output.
+ *   workspace_dev    device scratch of at least workspace_bytes, 256-byte aligned;
+ *                    owned by the caller, reusable by the next call on the same
+ *                    stream
+ *
+ * Errors (checked before anything is launched): ND_ERR_NULL_POINTER,
+ * ND_ERR_BAD_ARGUMENT, ND_ERR_NO_WEIGHTS, ND_ERR_WORKSPACE, ND_ERR_TOO_LARGE,
+ * ND_ERR_HIP.
+ */
+int nd_sample(const nd_graph* g, int app, const nd_params* params, const int32_t* roots_dev,
+              int64_t num_roots, uint64_t seed, int32_t* const* step_out_dev, void* workspace_dev,
+              size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Waits for hip_stream and reports what the last nd_sample that used this
+ * workspace recorded on the device: ND_OK, or ND_ERR_BAD_ROOT.
+ */
+int nd_sample_status(const void* workspace_dev, void* hip_stream);
+
+/*
+ * Per-step scheduling statistics of the last transit-parallel nd_sample on
+ * this workspace (waits for hip_stream).  stats receives, for each of the
+ * first max_steps steps, 8 int64 values: live pairs, distinct transits,
+ * transits in the sub-wavefront / workgroup / grid class, grid chunks,
+ * transits staged in LDS, reserved.  Evidence for Section 6.1.2's partition.
+ */
+int nd_sample_stats(const void* workspace_dev, void* hip_stream, int32_t max_steps,
+                    int64_t* stats);
+
+/*
+ * The scheduling-index build on its own (Section 6.1.2, "Scheduling"; Section
+ * 8.1): groups the live entries of a transit array by transit vertex.
+ *
+ *   transits_dev     device, n int32: transit of every slot (negative = no transit)
+ *   V                transits are < V
+ *   sorted_transits_dev, sorted_slots_dev   device, n int32 each: the live pairs
+ *                    ordered by transit, slots of equal transits ascending
+ *   group_transit_dev, group_start_dev      device, n and n+1 int32: distinct
+ *                    transits ascending and the position of each one's first pair;
+ *                    group_start[num_groups] = number of live pairs
+ *   counts_dev       device, 2 int64: number of live pairs, number of groups
+ *   workspace_dev    device scratch, nd_group_workspace_bytes(n, V) bytes
+ */
+size_t nd_group_workspace_bytes(int64_t n, int64_t V);
+int nd_group_by_transit(const int32_t* transits_dev, int64_t n, int64_t V,
+                        int32_t* sorted_transits_dev, int32_t* sorted_slots_dev,
+                        int32_t* group_transit_dev, int32_t* group_start_dev, int64_t* counts_dev,
+                        void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
+const char* nd_last_error(void);
+int nd_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ND_H_ */

@@ -1,0 +1,283 @@
+"""Thin ctypes binding of libnd.so: same names as include/nd.h, argument
+marshalling only.  PyTorch supplies device memory and the current stream;
+every step of the sampling path runs inside the library's HIP kernels.
+
+There is no CPU fallback: if the shared library is missing, loading fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libnd.so")
+
+ND_MAX_FANOUT_STEPS = 8
+ND_MAX_WALK_STEPS = 4096
+ND_NULL_VERTEX = -1
+
+ND_DEEPWALK, ND_PPR, ND_NODE2VEC, ND_KHOP, ND_LAYER = range(5)
+ND_MODE_TRANSIT_PARALLEL, ND_MODE_SAMPLE_PARALLEL = 0, 1
+ND_CLASS_AUTO, ND_CLASS_SUBWAVE, ND_CLASS_WORKGROUP, ND_CLASS_GRID = -1, 0, 1, 2
+
+ND_OK = 0
+ND_ERR_NULL_POINTER, ND_ERR_BAD_ARGUMENT, ND_ERR_BAD_GRAPH, ND_ERR_BAD_WEIGHT = -1, -2, -3, -4
+ND_ERR_NO_WEIGHTS, ND_ERR_WORKSPACE, ND_ERR_HIP, ND_ERR_BAD_ROOT, ND_ERR_TOO_LARGE = -5, -6, -7, -8, -9
+
+EXPORTS = ["nd_params_init", "nd_graph_create", "nd_graph_destroy", "nd_graph_info", "nd_sample_query",
+           "nd_sample", "nd_sample_status", "nd_sample_stats", "nd_group_workspace_bytes",
+           "nd_group_by_transit", "nd_last_error", "nd_version"]
+
+
+class nd_params(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", ctypes.c_uint32),
+        ("num_steps", ctypes.c_int32),
+        ("fanout", ctypes.c_int32 * ND_MAX_FANOUT_STEPS),
+        ("use_weights", ctypes.c_int32),
+        ("bias_convention", ctypes.c_int32),
+        ("p", ctypes.c_double),
+        ("q", ctypes.c_double),
+        ("term_prob", ctypes.c_double),
+        ("roots_per_sample", ctypes.c_int32),
+        ("n2v_max_attempts", ctypes.c_int32),
+        ("sample_id_base", ctypes.c_uint64),
+        ("mode", ctypes.c_int32),
+        ("sched_force_class", ctypes.c_int32),
+        ("sched_sub_max", ctypes.c_int32),
+        ("sched_wg_max", ctypes.c_int32),
+        ("lds_stage_policy", ctypes.c_int32),
+        ("reserved", ctypes.c_int32 * 5),
+    ]
+
+
+class NdError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"nd error {code}: {message}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Loads libnd.so (built in-tree by paper_2009_06693_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: run `python -m paper_2009_06693_amd.build` "
+                "(there is no CPU fallback)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, u64, sz = (ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint64,
+                                 ctypes.c_size_t)
+        L.nd_params_init.restype = None
+        L.nd_params_init.argtypes = [ctypes.POINTER(nd_params)]
+        L.nd_graph_create.restype = ctypes.c_int
+        L.nd_graph_create.argtypes = [ctypes.POINTER(vp), i64, i64, vp, ctypes.c_int, vp, vp,
+                                      ctypes.c_int, vp]
+        L.nd_graph_destroy.restype = ctypes.c_int
+        L.nd_graph_destroy.argtypes = [vp]
+        L.nd_graph_info.restype = ctypes.c_int
+        L.nd_graph_info.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i64),
+                                    ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
+        L.nd_sample_query.restype = ctypes.c_int
+        L.nd_sample_query.argtypes = [vp, ctypes.c_int, ctypes.POINTER(nd_params), i64,
+                                      ctypes.POINTER(i32), ctypes.POINTER(i64), ctypes.POINTER(sz)]
+        L.nd_sample.restype = ctypes.c_int
+        L.nd_sample.argtypes = [vp, ctypes.c_int, ctypes.POINTER(nd_params), vp, i64, u64,
+                                ctypes.POINTER(vp), vp, sz, vp]
+        L.nd_sample_status.restype = ctypes.c_int
+        L.nd_sample_status.argtypes = [vp, vp]
+        L.nd_sample_stats.restype = ctypes.c_int
+        L.nd_sample_stats.argtypes = [vp, vp, i32, ctypes.POINTER(i64)]
+        L.nd_group_workspace_bytes.restype = sz
+        L.nd_group_workspace_bytes.argtypes = [i64, i64]
+        L.nd_group_by_transit.restype = ctypes.c_int
+        L.nd_group_by_transit.argtypes = [vp, i64, i64, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.nd_last_error.restype = ctypes.c_char_p
+        L.nd_last_error.argtypes = []
+        L.nd_version.restype = ctypes.c_int
+        L.nd_version.argtypes = []
+        _lib = L
+    return _lib
+
+
+def _check(rc: int):
+    if rc != ND_OK:
+        raise NdError(rc, lib().nd_last_error().decode())
+
+
+def nd_version() -> int:
+    return lib().nd_version()
+
+
+def nd_params_init(**overrides) -> nd_params:
+    """Returns an nd_params with the library's defaults, then applies keyword overrides
+    (fanout may be given as a sequence)."""
+    p = nd_params()
+    lib().nd_params_init(ctypes.byref(p))
+    for k, v in overrides.items():
+        if k == "fanout":
+            for i, f in enumerate(v):
+                p.fanout[i] = int(f)
+        else:
+            if not hasattr(p, k):
+                raise AttributeError(k)
+            setattr(p, k, v)
+    return p
+
+
+def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return s.cuda_stream
+
+
+class Graph:
+    """Owner of an nd_graph handle."""
+
+    def __init__(self, handle: int, V: int, E: int, weighted: bool):
+        self._h = handle
+        self.V, self.E, self.weighted = V, E, weighted
+
+    def destroy(self):
+        if self._h:
+            lib().nd_graph_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def nd_graph_create(row_offsets, col_indices, weights=None, stream=None) -> Graph:
+    """row_offsets / col_indices / weights: numpy arrays (host) or CUDA tensors (device);
+    offsets int32 or int64, columns int32, weights float32."""
+    L = lib()
+    on_device = isinstance(row_offsets, torch.Tensor)
+    if on_device:
+        if not (row_offsets.is_cuda and col_indices.is_cuda and (weights is None or weights.is_cuda)):
+            raise ValueError("all graph tensors must be CUDA tensors")
+        off, col = row_offsets.contiguous(), col_indices.contiguous()
+        w = None if weights is None else weights.contiguous()
+        if col.dtype != torch.int32 or off.dtype not in (torch.int32, torch.int64):
+            raise TypeError("offsets must be int32/int64 and columns int32")
+        if w is not None and w.dtype != torch.float32:
+            raise TypeError("weights must be float32")
+        is64 = off.dtype == torch.int64
+        V, E = off.numel() - 1, col.numel()
+        ptrs = (off.data_ptr(), col.data_ptr(), None if w is None else w.data_ptr())
+    else:
+        off = np.ascontiguousarray(row_offsets)
+        col = np.ascontiguousarray(col_indices)
+        w = None if weights is None else np.ascontiguousarray(weights)
+        if col.dtype != np.int32 or off.dtype not in (np.int32, np.int64):
+            raise TypeError("offsets must be int32/int64 and columns int32")
+        if w is not None and w.dtype != np.float32:
+            raise TypeError("weights must be float32")
+        is64 = off.dtype == np.int64
+        V, E = off.shape[0] - 1, col.shape[0]
+        ptrs = (off.ctypes.data, col.ctypes.data, None if w is None else w.ctypes.data)
+        torch.cuda.init()
+    h = ctypes.c_void_p()
+    _check(L.nd_graph_create(ctypes.byref(h), V, E, ptrs[0], int(is64), ptrs[1], ptrs[2],
+                             int(on_device), _stream_ptr(stream)))
+    return Graph(h.value, V, E, weights is not None)
+
+
+def nd_graph_destroy(g: Graph):
+    g.destroy()
+
+
+def nd_sample_query(g: Graph, app: int, params: nd_params, num_roots: int):
+    """Returns (step_len list, workspace_bytes)."""
+    n = ctypes.c_int32()
+    lens = (ctypes.c_int64 * ND_MAX_WALK_STEPS)()
+    ws = ctypes.c_size_t()
+    _check(lib().nd_sample_query(g._h, app, ctypes.byref(params), num_roots, ctypes.byref(n), lens,
+                                 ctypes.byref(ws)))
+    return [int(lens[i]) for i in range(n.value)], int(ws.value)
+
+
+def nd_sample(g: Graph, app: int, params: nd_params, roots: torch.Tensor, seed: int,
+              step_out: Sequence[torch.Tensor], workspace: torch.Tensor, stream=None):
+    """Asynchronous on the stream; step_out[i] are caller-allocated int32 CUDA tensors."""
+    if roots.dtype != torch.int32 or not roots.is_cuda or not roots.is_contiguous():
+        raise TypeError("roots must be a contiguous int32 CUDA tensor")
+    for t in step_out:
+        if t.dtype != torch.int32 or not t.is_cuda or not t.is_contiguous():
+            raise TypeError("outputs must be contiguous int32 CUDA tensors")
+    arr = (ctypes.c_void_p * len(step_out))(*[t.data_ptr() for t in step_out])
+    _check(lib().nd_sample(g._h, app, ctypes.byref(params), roots.data_ptr(), roots.numel(), seed, arr,
+                           workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                           _stream_ptr(stream)))
+
+
+def nd_sample_status(workspace: torch.Tensor, stream=None):
+    _check(lib().nd_sample_status(workspace.data_ptr(), _stream_ptr(stream)))
+
+
+def nd_sample_stats(workspace: torch.Tensor, num_steps: int, stream=None) -> np.ndarray:
+    """int64 [num_steps, 8]: live pairs, distinct transits, sub-wavefront / workgroup / grid
+    transits, grid chunks, work items staged in LDS, reserved."""
+    out = (ctypes.c_int64 * (8 * num_steps))()
+    _check(lib().nd_sample_stats(workspace.data_ptr(), _stream_ptr(stream), num_steps, out))
+    return np.array(out, dtype=np.int64).reshape(num_steps, 8)
+
+
+def nd_group_by_transit(transits: torch.Tensor, V: int, stream=None):
+    """Returns (sorted_transits, sorted_slots, group_transit, group_start, num_pairs, num_groups)."""
+    if transits.dtype != torch.int32 or not transits.is_cuda:
+        raise TypeError("transits must be an int32 CUDA tensor")
+    n = transits.numel()
+    dev = transits.device
+    sk = torch.empty(max(n, 1), dtype=torch.int32, device=dev)
+    sv = torch.empty(max(n, 1), dtype=torch.int32, device=dev)
+    gk = torch.empty(max(n, 1), dtype=torch.int32, device=dev)
+    gs = torch.empty(n + 1, dtype=torch.int32, device=dev)
+    counts = torch.zeros(2, dtype=torch.int64, device=dev)
+    wsb = lib().nd_group_workspace_bytes(n, V)
+    ws = torch.empty(wsb, dtype=torch.uint8, device=dev)
+    _check(lib().nd_group_by_transit(transits.contiguous().data_ptr(), n, V, sk.data_ptr(),
+                                     sv.data_ptr(), gk.data_ptr(), gs.data_ptr(), counts.data_ptr(),
+                                     ws.data_ptr(), wsb, _stream_ptr(stream)))
+    c = counts.cpu()
+    P, U = int(c[0]), int(c[1])
+    return sk[:P], sv[:P], gk[:U], gs[:U + 1], P, U
+
+
+# ---------------------------------------------------------------------------
+# Convenience wrapper used by tests, smoke and the benchmark: allocates the
+# outputs and workspace with torch and calls nd_sample.
+# ---------------------------------------------------------------------------
+
+class Sampler:
+    def __init__(self, g: Graph, app: int, params: nd_params, num_roots: int, device="cuda:0"):
+        self.g, self.app, self.params, self.num_roots = g, app, params, num_roots
+        self.step_len, self.workspace_bytes = nd_sample_query(g, app, params, num_roots)
+        self.device = torch.device(device)
+        self.workspace = torch.empty(max(self.workspace_bytes, 256), dtype=torch.uint8,
+                                     device=self.device)
+        total = sum(self.step_len)
+        self._flat = torch.empty(max(total, 1), dtype=torch.int32, device=self.device)
+        self.out: List[torch.Tensor] = []
+        base = 0
+        for n in self.step_len:
+            self.out.append(self._flat[base:base + n])
+            base += n
+
+    def run(self, roots: torch.Tensor, seed: int, stream=None) -> List[torch.Tensor]:
+        nd_sample(self.g, self.app, self.params, roots, seed, self.out, self.workspace, stream)
+        return self.out
+
+    def status(self):
+        nd_sample_status(self.workspace)
+
+    def stats(self) -> np.ndarray:
+        return nd_sample_stats(self.workspace, len(self.step_len))

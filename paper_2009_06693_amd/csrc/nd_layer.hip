@@ -1,0 +1,103 @@
+// Collective transit sampling (Section 6.2 of the paper; layer sampling with
+// LADIES-style importance weights, Section 4.2 "Importance Sampling").
+//
+// The paper materialises every sample's combined neighbourhood in global
+// memory (transit-parallel copy of whole adjacency lists) and then draws from
+// it sample-parallel.  On this GPU the copy is the dominant traffic, so the
+// combined neighbourhood stays implicit: it is the concatenation, in slot
+// order, of the transits' adjacency lists, described by a running sum of
+// per-transit masses deg(v) * c(v) kept in LDS; a draw picks a position in the
+// concatenation by inverse transform (binary search over the running sums,
+// then an integer division by c(v) inside the chosen list) and reads that one
+// neighbour.  One workgroup per sample, as in the paper's sample-parallel draw.
+//
+// c(v) = floor(2^48 / deg(v)^2) is the fixed-point squared entry of the
+// row-normalised adjacency matrix, so a vertex is drawn with probability
+// proportional to its squared column norm restricted to the transit rows.
+#include "nd_common.h"
+#include "nd_philox.h"
+#include "nd_sample.h"
+#include "nd_wave.h"
+
+namespace nd {
+
+namespace {
+
+constexpr int kLayerThreads = 256;
+
+template <typename OffT>
+__global__ __launch_bounds__(kLayerThreads) void layer_kernel(GraphView<OffT> g, LayerArgs a) {
+    __shared__ uint64_t s_incl[ND_MAX_LAYER_TRANSITS];
+    __shared__ uint64_t s_c[ND_MAX_LAYER_TRANSITS];
+    __shared__ int32_t s_v[ND_MAX_LAYER_TRANSITS];
+    __shared__ uint64_t scan_tmp[kLayerThreads / 64 + 1];
+    const uint32_t b = blockIdx.x;
+    const int32_t* transits = a.transits + (uint64_t)b * a.n_prev;
+
+    uint64_t carry = 0;
+    bool bad = false;
+    for (uint32_t base = 0; base < a.n_prev; base += kLayerThreads) {
+        const uint32_t t = base + threadIdx.x;
+        uint64_t mass = 0, c = 0;
+        int32_t v = ND_NULL_VERTEX;
+        if (t < a.n_prev) {
+            v = transits[t];
+            if (v >= g.V || v < ND_NULL_VERTEX) {
+                bad = true;
+                v = ND_NULL_VERTEX;
+            }
+            if (v >= 0) {
+                const uint64_t deg = (uint64_t)g.off[v + 1] - (uint64_t)g.off[v];
+                if (deg > 0) {
+                    c = (1ull << 48) / (deg * deg);
+                    mass = deg * c;
+                }
+            }
+        }
+        uint64_t total;
+        const uint64_t ex = block_exclusive_scan<uint64_t, kLayerThreads>(mass, scan_tmp, &total);
+        if (t < a.n_prev) {
+            s_incl[t] = carry + ex + mass;
+            s_c[t] = c;
+            s_v[t] = v;
+        }
+        carry += total;
+        __syncthreads();
+    }
+    if (a.check_roots && bad) atomicOr(a.status, 1u);
+    const uint64_t total = carry;
+
+    for (uint32_t j = threadIdx.x; j < a.m; j += kLayerThreads) {
+        int32_t res = ND_NULL_VERTEX;
+        if (total > 0) {
+            const Rand4 r = draw4(a.seed, a.sample_base + b, j, a.step, 0u);
+            const uint64_t x = mulhi64(cat64(r.r0, r.r1), total);
+            uint32_t lo = 0, hi = a.n_prev - 1;
+            while (lo < hi) {  // first transit whose running sum exceeds x
+                const uint32_t mid = (lo + hi) >> 1;
+                if (s_incl[mid] > x) hi = mid;
+                else lo = mid + 1;
+            }
+            const uint64_t before = lo ? s_incl[lo - 1] : 0ull;
+            const uint64_t idx = (x - before) / s_c[lo];
+            res = g.col[(uint64_t)g.off[s_v[lo]] + idx];
+        }
+        a.out[(uint64_t)b * a.m + j] = res;
+    }
+}
+
+}  // namespace
+
+int layer_step(const Graph& gr, const LayerArgs& a, int64_t num_samples, hipStream_t stream) {
+    if (num_samples == 0) return ND_OK;
+    if (gr.off64)
+        hipLaunchKernelGGL(layer_kernel<int64_t>, dim3((unsigned)num_samples), dim3(kLayerThreads), 0,
+                           stream, view_of<int64_t>(gr), a);
+    else
+        hipLaunchKernelGGL(layer_kernel<int32_t>, dim3((unsigned)num_samples), dim3(kLayerThreads), 0,
+                           stream, view_of<int32_t>(gr), a);
+    ND_HIP_CHECK(hipGetLastError());
+    return ND_OK;
+}
+
+}  // namespace nd

@@ -1,0 +1,401 @@
+// Sampling kernels for individual transit sampling (random walks and k-hop;
+// Section 6.1 of the paper).
+//
+// Three transit-parallel kernels, one per scheduling class of Section 6.1.2
+// (Table "Types of kernels"), re-derived for 64-lane wavefronts:
+//   sub-wavefront  64 consecutive transits share a wavefront; every draw gets a
+//                  lane, the draws of one (transit, sample) pair sit on
+//                  consecutive lanes so the sample's new vertices leave in one
+//                  contiguous store (the paper's sub-warps, Section 6.1.1);
+//                  per-transit data is fetched once per transit and handed to
+//                  the drawing lanes through LDS.
+//   workgroup      one 256-lane workgroup per transit; the adjacency list (and
+//                  the weight running sums) are staged in LDS when they fit and
+//                  the reuse pays for the copy, otherwise read from global
+//                  memory ("Caching", Section 6.1.2).
+//   grid           a transit with more draws than one workgroup handles is cut
+//                  into chunks, one workgroup each, every chunk staging the list.
+// plus the sample-parallel kernel of Section 5.1 (one lane per output slot, no
+// grouping), kept as the ablation baseline.
+//
+// What a lane draws is the same in all four: one Philox call per
+// (sample, slot, step, attempt), so the four produce identical outputs.
+#include "nd_common.h"
+#include "nd_philox.h"
+#include "nd_wave.h"
+#include "nd_sample.h"
+
+namespace nd {
+
+namespace {
+
+constexpr uint32_t kOneQ16 = 65536u;
+
+// ---------------------------------------------------------------- one draw
+// adj / cum / wq point at the transit's row (global memory or its LDS copy).
+
+template <typename OffT>
+__device__ __forceinline__ bool row_contains(const GraphView<OffT>& g, uint64_t rs, uint32_t deg,
+                                             int32_t u) {
+    uint32_t lo = 0, hi = deg;
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;
+        const int32_t c = g.col[rs + mid];
+        if (c < u) lo = mid + 1;
+        else hi = mid;
+    }
+    return lo < deg && g.col[rs + lo] == u;
+}
+
+// Uniform neighbour (DeepWalk, PPR, k-hop): index = high word of R0 * degree.
+__device__ __forceinline__ int32_t draw_uniform(const DrawArgs& a, uint32_t deg, uint32_t sid,
+                                                uint32_t slot, const int32_t* adj) {
+    const Rand4 r = draw4(a.seed, sid, slot, a.step, 0u);
+    if (a.ppr_thr != 0 && (uint64_t)r.r3 < a.ppr_thr) return ND_NULL_VERTEX;
+    return adj[mulhi32(r.r0, deg)];
+}
+
+// Weight-proportional neighbour: inverse transform on the row's running sums.
+__device__ __forceinline__ int32_t draw_weighted(const DrawArgs& a, uint32_t deg, uint32_t sid,
+                                                 uint32_t slot, const int32_t* adj,
+                                                 const uint64_t* cum) {
+    const Rand4 r = draw4(a.seed, sid, slot, a.step, 0u);
+    if (a.ppr_thr != 0 && (uint64_t)r.r3 < a.ppr_thr) return ND_NULL_VERTEX;
+    const uint64_t x = mulhi64(cat64(r.r0, r.r1), cum[deg - 1]);
+    uint32_t lo = 0, hi = deg - 1;
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (cum[mid] > x) hi = mid;
+        else lo = mid + 1;
+    }
+    return adj[lo];
+}
+
+// node2vec (Section 4.2): rejection sampling under the envelope
+// maxEdgeWeight(v) * largest bias; the bias of candidate u depends on its
+// relation to t, the transit of the previous step.  The membership search in
+// t's row is skipped when both possible biases give the same verdict.
+template <typename OffT>
+__device__ __forceinline__ uint32_t n2v_bias(const GraphView<OffT>& g, const DrawArgs& a, int32_t t,
+                                             uint64_t rs_t, uint32_t deg_t, int32_t u) {
+    if (!a.has_prev) return kOneQ16;
+    if (u == t) return a.b_ret;
+    return row_contains(g, rs_t, deg_t, u) ? a.b_com : a.b_far;
+}
+
+template <typename OffT>
+__device__ __forceinline__ int32_t draw_node2vec(const GraphView<OffT>& g, const DrawArgs& a,
+                                                 int32_t v, uint32_t deg, uint32_t sid,
+                                                 uint32_t s_index, const int32_t* adj,
+                                                 const uint32_t* wq) {
+    const uint32_t maxw = a.use_weights ? g.maxwq[v] : kOneQ16;
+    const uint64_t envelope = (uint64_t)maxw * (a.has_prev ? a.b_max : kOneQ16);
+    int32_t t = ND_NULL_VERTEX;
+    uint64_t rs_t = 0;
+    uint32_t deg_t = 0;
+    if (a.has_prev) {
+        t = a.prev_transit[s_index];
+        rs_t = (uint64_t)g.off[t];
+        deg_t = (uint32_t)((uint64_t)g.off[t + 1] - rs_t);
+    }
+    const uint32_t b_lo = a.b_com < a.b_far ? a.b_com : a.b_far;
+    const uint32_t b_hi = a.b_com < a.b_far ? a.b_far : a.b_com;
+    for (int32_t att = 0; att < a.max_attempts; ++att) {
+        const Rand4 r = draw4(a.seed, sid, 0u, a.step, (uint32_t)att);
+        const uint32_t e = mulhi32(r.r0, deg);
+        const int32_t u = adj[e];
+        const uint64_t y = mulhi64(cat64(r.r1, r.r2), envelope);
+        const uint64_t w = a.use_weights ? wq[e] : kOneQ16;
+        if (!a.has_prev) {
+            if (y < w * kOneQ16) return u;
+        } else if (u == t) {
+            if (y < w * a.b_ret) return u;
+        } else if (y < w * b_lo) {
+            return u;
+        } else if (y < w * b_hi) {
+            const uint32_t bias = row_contains(g, rs_t, deg_t, u) ? a.b_com : a.b_far;
+            if (y < w * bias) return u;
+        }
+    }
+    // exact fallback: inverse transform over all biased weights of the row
+    const Rand4 r = draw4(a.seed, sid, 0u, a.step, (uint32_t)a.max_attempts);
+    uint64_t Z = 0;
+    for (uint32_t e = 0; e < deg; ++e) {
+        const uint64_t w = a.use_weights ? wq[e] : kOneQ16;
+        Z += w * n2v_bias(g, a, t, rs_t, deg_t, adj[e]);
+    }
+    const uint64_t x = mulhi64(cat64(r.r0, r.r1), Z);
+    uint64_t run = 0;
+    for (uint32_t e = 0; e < deg; ++e) {
+        const uint64_t w = a.use_weights ? wq[e] : kOneQ16;
+        run += w * n2v_bias(g, a, t, rs_t, deg_t, adj[e]);
+        if (run > x) return adj[e];
+    }
+    return adj[deg - 1];  // not reached: x < Z
+}
+
+// q: slot of the transit in the previous step's array; jj: which of its m draws.
+template <int DRAW, typename OffT>
+__device__ __forceinline__ int32_t draw_for_slot(const GraphView<OffT>& g, const DrawArgs& a,
+                                                 int32_t v, uint32_t deg, uint32_t q, uint32_t jj,
+                                                 const int32_t* adj, const uint64_t* cum,
+                                                 const uint32_t* wq) {
+    const uint32_t s = fastdiv(q, a.div_wprev);
+    const uint32_t slot = (q - s * a.div_wprev.d) * a.m + jj;
+    const uint32_t sid = a.sample_base + s;
+    if (DRAW == kDrawUniform) return draw_uniform(a, deg, sid, slot, adj);
+    if (DRAW == kDrawWeighted) return draw_weighted(a, deg, sid, slot, adj, cum);
+    return draw_node2vec(g, a, v, deg, sid, s, adj, wq);
+}
+
+// ---------------------------------------------------------------- sample-parallel (Section 5.1)
+template <int DRAW, typename OffT>
+__global__ __launch_bounds__(256) void sample_sp_kernel(GraphView<OffT> g, DrawArgs a,
+                                                        const int32_t* __restrict__ src,
+                                                        int64_t n_slots, int check_roots,
+                                                        uint32_t* __restrict__ status) {
+    const int64_t o = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (o >= n_slots * (int64_t)a.m) return;
+    const uint32_t q = fastdiv((uint32_t)o, a.div_m);
+    const uint32_t jj = (uint32_t)o - q * a.m;
+    int32_t v = src[q];
+    if (v >= g.V || v < ND_NULL_VERTEX) {
+        if (check_roots) atomicOr(status, 1u);
+        v = ND_NULL_VERTEX;
+    }
+    int32_t res = ND_NULL_VERTEX;
+    if (v >= 0) {
+        const uint64_t rs = (uint64_t)g.off[v];
+        const uint32_t deg = (uint32_t)((uint64_t)g.off[v + 1] - rs);
+        if (deg > 0)
+            res = draw_for_slot<DRAW>(g, a, v, deg, q, jj, g.col + rs,
+                                      DRAW == kDrawWeighted ? g.cumq + rs : nullptr,
+                                      (DRAW == kDrawNode2vec && a.use_weights) ? g.wq + rs : nullptr);
+    }
+    a.out[o] = res;
+}
+
+// ---------------------------------------------------------------- sub-wavefront class
+
+template <int DRAW, typename OffT>
+__global__ __launch_bounds__(256) void sample_sub_kernel(GraphView<OffT> g, DrawArgs a,
+                                                         SchedParams sp,
+                                                         const StepCtl* __restrict__ ctl,
+                                                         const int32_t* __restrict__ g_key,
+                                                         const int32_t* __restrict__ g_start,
+                                                         const int32_t* __restrict__ vals) {
+    __shared__ uint32_t s_off[4][65];
+    __shared__ uint32_t s_start[4][64];
+    __shared__ uint32_t s_deg[4][64];
+    __shared__ int32_t s_key[4][64];
+    __shared__ uint64_t s_rs[4][64];
+    const int lane = lane_id(), wave = wave_id();
+    const uint32_t U = ctl->U;
+    const uint32_t n_chunks = (U + 63u) >> 6;
+    const uint32_t wave_gid = blockIdx.x * 4u + (uint32_t)wave;
+    const uint32_t n_waves = gridDim.x * 4u;
+    for (uint32_t c = wave_gid; c < n_chunks; c += n_waves) {
+        // phase 1: one lane per transit
+        const uint32_t gi = c * 64u + (uint32_t)lane;
+        uint32_t draws = 0, start = 0, deg = 0;
+        uint64_t rs = 0;
+        int32_t v = ND_NULL_VERTEX;
+        if (gi < U) {
+            start = (uint32_t)g_start[gi];
+            const uint32_t size = (uint32_t)g_start[gi + 1] - start;
+            if (class_of(size * a.m, sp) == ND_CLASS_SUBWAVE) {
+                draws = size * a.m;
+                v = g_key[gi];
+                rs = (uint64_t)g.off[v];
+                deg = (uint32_t)((uint64_t)g.off[v + 1] - rs);
+            }
+        }
+        const uint32_t incl = wave_inclusive_scan(draws, lane);
+        const uint32_t total = __shfl(incl, 63, 64);
+        if (total == 0) continue;
+        s_off[wave][lane] = incl - draws;
+        if (lane == 63) s_off[wave][64] = total;
+        s_start[wave][lane] = start;
+        s_deg[wave][lane] = deg;
+        s_key[wave][lane] = v;
+        s_rs[wave][lane] = rs;
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        // phase 2: one lane per draw
+        for (uint32_t d = (uint32_t)lane; d < total; d += 64u) {
+            // owner = last transit whose first draw is at or before d
+            uint32_t lo = 0, hi = 64;
+#pragma unroll
+            for (int it = 0; it < 6; ++it) {
+                const uint32_t mid = (lo + hi) >> 1;
+                if (s_off[wave][mid] <= d) lo = mid;
+                else hi = mid;
+            }
+            const uint32_t rel = d - s_off[wave][lo];
+            const uint32_t pi = fastdiv(rel, a.div_m);
+            const uint32_t jj = rel - pi * a.m;
+            const uint32_t q = (uint32_t)vals[s_start[wave][lo] + pi];
+            const uint32_t dg = s_deg[wave][lo];
+            int32_t res = ND_NULL_VERTEX;
+            if (dg > 0) {
+                const uint64_t r0 = s_rs[wave][lo];
+                res = draw_for_slot<DRAW>(g, a, s_key[wave][lo], dg, q, jj, g.col + r0,
+                                          DRAW == kDrawWeighted ? g.cumq + r0 : nullptr,
+                                          (DRAW == kDrawNode2vec && a.use_weights) ? g.wq + r0 : nullptr);
+            }
+            a.out[(uint64_t)q * a.m + jj] = res;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    }
+}
+
+// ---------------------------------------------------------------- workgroup and grid classes
+template <int DRAW>
+struct StageCap {
+    static constexpr uint32_t value = DRAW == kDrawUniform ? 12288u : (DRAW == kDrawWeighted ? 4096u : 6144u);
+};
+
+// Draws d in [d0, d1) of group gid, by one 256-lane workgroup.
+template <int DRAW, typename OffT>
+__device__ __forceinline__ void workgroup_draws(const GraphView<OffT>& g, const DrawArgs& a,
+                                                StepCtl* ctl, const int32_t* __restrict__ g_key,
+                                                const int32_t* __restrict__ g_start,
+                                                const int32_t* __restrict__ vals, uint32_t gid,
+                                                uint32_t d0, uint32_t d1, int32_t* lds_col,
+                                                uint64_t* lds_cum, uint32_t* lds_wq) {
+    constexpr uint32_t cap = StageCap<DRAW>::value;
+    const int32_t v = g_key[gid];
+    const uint32_t start = (uint32_t)g_start[gid];
+    const uint64_t rs = (uint64_t)g.off[v];
+    const uint32_t deg = (uint32_t)((uint64_t)g.off[v + 1] - rs);
+    const uint32_t ndraws = d1 - d0;
+    bool stage = deg > 0 && deg <= cap;
+    if (a.lds_policy == 1) stage = false;
+    else if (a.lds_policy == 0) stage = stage && deg <= 16u * ndraws;
+    const int32_t* adj = g.col + rs;
+    const uint64_t* cum = DRAW == kDrawWeighted ? g.cumq + rs : nullptr;
+    const uint32_t* wq = (DRAW == kDrawNode2vec && a.use_weights) ? g.wq + rs : nullptr;
+    if (stage) {
+        for (uint32_t i = threadIdx.x; i < deg; i += 256u) {
+            lds_col[i] = adj[i];
+            if (DRAW == kDrawWeighted) lds_cum[i] = cum[i];
+            if (DRAW == kDrawNode2vec && a.use_weights) lds_wq[i] = wq[i];
+        }
+        if (threadIdx.x == 0) atomicAdd(&ctl->n_staged, 1u);
+        __syncthreads();
+        adj = lds_col;
+        if (DRAW == kDrawWeighted) cum = lds_cum;
+        if (DRAW == kDrawNode2vec && a.use_weights) wq = lds_wq;
+    }
+    for (uint32_t d = d0 + threadIdx.x; d < d1; d += 256u) {
+        const uint32_t pi = fastdiv(d, a.div_m);
+        const uint32_t jj = d - pi * a.m;
+        const uint32_t q = (uint32_t)vals[start + pi];
+        int32_t res = ND_NULL_VERTEX;
+        if (deg > 0) res = draw_for_slot<DRAW>(g, a, v, deg, q, jj, adj, cum, wq);
+        a.out[(uint64_t)q * a.m + jj] = res;
+    }
+    __syncthreads();  // the LDS copy is reused by the next work item
+}
+
+template <int DRAW, typename OffT, bool GRID>
+__global__ __launch_bounds__(256) void sample_wg_kernel(GraphView<OffT> g, DrawArgs a, SchedParams sp,
+                                                        StepCtl* __restrict__ ctl,
+                                                        const int32_t* __restrict__ g_key,
+                                                        const int32_t* __restrict__ g_start,
+                                                        const int32_t* __restrict__ vals,
+                                                        const int32_t* __restrict__ list,
+                                                        const int32_t* __restrict__ chunk_idx,
+                                                        uint32_t list_capacity) {
+    constexpr uint32_t cap = StageCap<DRAW>::value;
+    __shared__ int32_t lds_col[cap];
+    __shared__ uint64_t lds_cum[DRAW == kDrawWeighted ? cap : 1];
+    __shared__ uint32_t lds_wq[DRAW == kDrawNode2vec ? cap : 1];
+    uint32_t n_items = GRID ? ctl->n_chunks : ctl->n_wg;
+    if (n_items > list_capacity) n_items = list_capacity;  // the lists are sized so this never bites
+    for (uint32_t i = blockIdx.x; i < n_items; i += gridDim.x) {
+        const uint32_t gid = (uint32_t)list[i];
+        const uint32_t size = (uint32_t)(g_start[gid + 1] - g_start[gid]);
+        const uint32_t draws = size * a.m;
+        uint32_t d0 = 0, d1 = draws;
+        if (GRID) {
+            d0 = (uint32_t)chunk_idx[i] * (uint32_t)sp.wg_max;
+            d1 = d0 + (uint32_t)sp.wg_max < draws ? d0 + (uint32_t)sp.wg_max : draws;
+        }
+        workgroup_draws<DRAW, OffT>(g, a, ctl, g_key, g_start, vals, gid, d0, d1, lds_col, lds_cum,
+                                    lds_wq);
+    }
+}
+
+template <int DRAW, typename OffT>
+int launch_tp(const Graph& gr, const DrawArgs& a, const SchedParams& sp, StepCtl* ctl,
+              const int32_t* g_key, const int32_t* g_start, const int32_t* vals,
+              const int32_t* list_wg, const int32_t* chunk_gid, const int32_t* chunk_idx,
+              int64_t max_groups, int64_t max_wg, int64_t max_chunks, int64_t cap_wg,
+              int64_t cap_chunks, int num_cus, hipStream_t stream) {
+    const GraphView<OffT> g = view_of<OffT>(gr);
+    const int64_t persistent = (int64_t)num_cus * 8;
+    int64_t sub_blocks = (max_groups + 255) / 256;
+    sub_blocks = sub_blocks < 1 ? 1 : (sub_blocks > persistent ? persistent : sub_blocks);
+    int64_t wg_blocks = max_wg < 1 ? 1 : (max_wg > persistent ? persistent : max_wg);
+    int64_t grid_blocks = max_chunks < 1 ? 1 : (max_chunks > persistent ? persistent : max_chunks);
+    if (sp.force_class == ND_CLASS_AUTO || sp.force_class == ND_CLASS_GRID)
+        hipLaunchKernelGGL((sample_wg_kernel<DRAW, OffT, true>), dim3((unsigned)grid_blocks), dim3(256),
+                           0, stream, g, a, sp, ctl, g_key, g_start, vals, chunk_gid, chunk_idx,
+                           (uint32_t)cap_chunks);
+    if (sp.force_class == ND_CLASS_AUTO || sp.force_class == ND_CLASS_WORKGROUP)
+        hipLaunchKernelGGL((sample_wg_kernel<DRAW, OffT, false>), dim3((unsigned)wg_blocks), dim3(256),
+                           0, stream, g, a, sp, ctl, g_key, g_start, vals, list_wg,
+                           (const int32_t*)nullptr, (uint32_t)cap_wg);
+    if (sp.force_class == ND_CLASS_AUTO || sp.force_class == ND_CLASS_SUBWAVE)
+        hipLaunchKernelGGL((sample_sub_kernel<DRAW, OffT>), dim3((unsigned)sub_blocks), dim3(256), 0,
+                           stream, g, a, sp, ctl, g_key, g_start, vals);
+    ND_HIP_CHECK(hipGetLastError());
+    return ND_OK;
+}
+
+template <int DRAW, typename OffT>
+int launch_sp(const Graph& gr, const DrawArgs& a, const int32_t* src, int64_t n_slots,
+              int check_roots, uint32_t* status, hipStream_t stream) {
+    const GraphView<OffT> g = view_of<OffT>(gr);
+    const int64_t total = n_slots * (int64_t)a.m;
+    if (total == 0) return ND_OK;
+    const int64_t blocks = (total + 255) / 256;
+    hipLaunchKernelGGL((sample_sp_kernel<DRAW, OffT>), dim3((unsigned)blocks), dim3(256), 0, stream, g,
+                       a, src, n_slots, check_roots, status);
+    ND_HIP_CHECK(hipGetLastError());
+    return ND_OK;
+}
+
+}  // namespace
+
+#define ND_DISPATCH(DRAWV, CALL)                                                         \
+    do {                                                                                 \
+        if (gr.off64) {                                                                  \
+            using OffT = int64_t;                                                        \
+            if ((DRAWV) == kDrawUniform) { constexpr int D = kDrawUniform; return CALL; } \
+            if ((DRAWV) == kDrawWeighted) { constexpr int D = kDrawWeighted; return CALL; } \
+            { constexpr int D = kDrawNode2vec; return CALL; }                            \
+        } else {                                                                         \
+            using OffT = int32_t;                                                        \
+            if ((DRAWV) == kDrawUniform) { constexpr int D = kDrawUniform; return CALL; } \
+            if ((DRAWV) == kDrawWeighted) { constexpr int D = kDrawWeighted; return CALL; } \
+            { constexpr int D = kDrawNode2vec; return CALL; }                            \
+        }                                                                                \
+    } while (0)
+
+int sample_step_tp(const Graph& gr, int draw, const DrawArgs& a, const SchedParams& sp, StepCtl* ctl,
+                   const int32_t* g_key, const int32_t* g_start, const int32_t* vals,
+                   const int32_t* list_wg, const int32_t* chunk_gid, const int32_t* chunk_idx,
+                   int64_t max_groups, int64_t max_wg, int64_t max_chunks, int64_t cap_wg,
+                   int64_t cap_chunks, int num_cus, hipStream_t stream) {
+    ND_DISPATCH(draw, (launch_tp<D, OffT>(gr, a, sp, ctl, g_key, g_start, vals, list_wg, chunk_gid,
+                                          chunk_idx, max_groups, max_wg, max_chunks, cap_wg,
+                                          cap_chunks, num_cus, stream)));
+}
+
+int sample_step_sp(const Graph& gr, int draw, const DrawArgs& a, const int32_t* src, int64_t n_slots,
+                   int check_roots, uint32_t* status, hipStream_t stream) {
+    ND_DISPATCH(draw, (launch_sp<D, OffT>(gr, a, src, n_slots, check_roots, status, stream)));
+}
+
+}  // namespace nd

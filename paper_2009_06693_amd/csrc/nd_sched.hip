@@ -1,0 +1,200 @@
+// Scheduling index (Section 6.1.2 of the paper, "Scheduling"): from the pairs
+// sorted by transit, (1) a segmented scan finds the distinct transits with the
+// position and size of each one's group of samples, and (2) every transit is
+// assigned to one of three classes by the number of neighbours it must
+// produce; the workgroup and grid classes get compacted work lists, and the
+// position of a transit in its list is its scheduling index.  All counts stay
+// in device memory (StepCtl): the host never waits for them.
+#include "nd_common.h"
+#include "nd_wave.h"
+
+namespace nd {
+
+size_t seg_scratch_bytes(int64_t n_slots) {
+    const int64_t tiles = (n_slots + kSegTile - 1) / kSegTile + 1;
+    return (size_t)tiles * sizeof(uint32_t);
+}
+
+namespace {
+
+constexpr int kSegWaves = kSegThreads / 64;
+constexpr int kSegPerWave = kSegTile / kSegWaves;
+
+// A pair is the head of its group when its transit differs from the previous pair's.
+__device__ __forceinline__ bool is_head(const int32_t* __restrict__ keys, int64_t idx, int64_t P,
+                                        int lane, int32_t* key_out) {
+    int32_t k = idx < P ? keys[idx] : -2;
+    int32_t prev = __shfl_up(k, 1, 64);
+    if (lane == 0) prev = (idx > 0 && idx < P) ? keys[idx - 1] : -3;
+    *key_out = k;
+    return idx < P && k != prev;
+}
+
+__global__ __launch_bounds__(kSegThreads) void seg_count_kernel(const int32_t* __restrict__ keys,
+                                                                const StepCtl* __restrict__ ctl,
+                                                                uint32_t* __restrict__ tile_counts) {
+    __shared__ uint32_t wsum[kSegWaves];
+    const int lane = lane_id(), wave = wave_id();
+    const int64_t P = ctl->P;
+    const int64_t base = (int64_t)blockIdx.x * kSegTile + (int64_t)wave * kSegPerWave;
+    uint32_t cnt = 0;
+    if ((int64_t)blockIdx.x * kSegTile < P) {
+        for (int r = 0; r < kSegPerWave / 64; ++r) {
+            int32_t k;
+            const bool h = is_head(keys, base + r * 64 + lane, P, lane, &k);
+            cnt += (uint32_t)__popcll(__ballot(h));
+        }
+    }
+    if (lane == 0) wsum[wave] = cnt;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t t = 0;
+        for (int w = 0; w < kSegWaves; ++w) t += wsum[w];
+        tile_counts[blockIdx.x] = t;
+    }
+}
+
+// One workgroup: exclusive scan of the per-tile head counts in place, publishes
+// the number of groups and resets the class counters of the step.
+__global__ __launch_bounds__(1024) void seg_scan_kernel(uint32_t* __restrict__ tile_counts,
+                                                        int64_t num_tiles, StepCtl* __restrict__ ctl,
+                                                        int32_t* __restrict__ g_start) {
+    __shared__ uint32_t tmp[18];
+    uint32_t carry = 0;
+    for (int64_t base = 0; base < num_tiles; base += 1024) {
+        const int64_t i = base + threadIdx.x;
+        const uint32_t x = i < num_tiles ? tile_counts[i] : 0u;
+        uint32_t total;
+        const uint32_t ex = block_exclusive_scan<uint32_t, 1024>(x, tmp, &total);
+        if (i < num_tiles) tile_counts[i] = carry + ex;
+        carry += total;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        ctl->U = carry;
+        ctl->n_wg = 0;
+        ctl->n_grid = 0;
+        ctl->n_chunks = 0;
+        ctl->n_sub = 0;
+        ctl->n_staged = 0;
+        g_start[carry] = (int32_t)ctl->P;  // sentinel: end of the last group
+    }
+}
+
+__global__ __launch_bounds__(kSegThreads) void seg_write_kernel(const int32_t* __restrict__ keys,
+                                                                const StepCtl* __restrict__ ctl,
+                                                                const uint32_t* __restrict__ tile_offs,
+                                                                int32_t* __restrict__ g_key,
+                                                                int32_t* __restrict__ g_start) {
+    __shared__ uint32_t wsum[kSegWaves];
+    const int lane = lane_id(), wave = wave_id();
+    const int64_t P = ctl->P;
+    if ((int64_t)blockIdx.x * kSegTile >= P) return;
+    const int64_t base = (int64_t)blockIdx.x * kSegTile + (int64_t)wave * kSegPerWave;
+    // pass 1: heads per wave
+    uint32_t cnt = 0;
+    for (int r = 0; r < kSegPerWave / 64; ++r) {
+        int32_t k;
+        const bool h = is_head(keys, base + r * 64 + lane, P, lane, &k);
+        cnt += (uint32_t)__popcll(__ballot(h));
+    }
+    if (lane == 0) wsum[wave] = cnt;
+    __syncthreads();
+    uint32_t gid = tile_offs[blockIdx.x];
+    for (int w = 0; w < wave; ++w) gid += wsum[w];
+    // pass 2: group ids by ballot prefix (keys are in cache from pass 1)
+    for (int r = 0; r < kSegPerWave / 64; ++r) {
+        int32_t k;
+        const int64_t idx = base + r * 64 + lane;
+        const bool h = is_head(keys, idx, P, lane, &k);
+        const uint64_t bal = __ballot(h);
+        if (h) {
+            const uint32_t g = gid + (uint32_t)__popcll(bal & lanes_below(lane));
+            g_key[g] = k;
+            g_start[g] = (int32_t)idx;
+        }
+        gid += (uint32_t)__popcll(bal);
+    }
+}
+
+
+// One lane per transit.  Lanes of a wave reserve list space with one atomic per
+// class (wave-aggregated with ballots), so list order follows transit order
+// within a wave.
+__global__ __launch_bounds__(256) void classify_kernel(const int32_t* __restrict__ g_start,
+                                                       StepCtl* __restrict__ ctl, SchedParams sp,
+                                                       int32_t* __restrict__ list_wg,
+                                                       int32_t* __restrict__ chunk_gid,
+                                                       int32_t* __restrict__ chunk_idx,
+                                                       int64_t max_chunks) {
+    const int lane = lane_id();
+    const int64_t U = ctl->U;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t base = (int64_t)blockIdx.x * blockDim.x; base < U; base += stride) {
+        const int64_t g = base + threadIdx.x;
+        int cls = -1;
+        uint32_t draws = 0;
+        if (g < U) {
+            draws = (uint32_t)(g_start[g + 1] - g_start[g]) * (uint32_t)sp.m;
+            cls = class_of(draws, sp);
+        }
+        const uint64_t b_sub = __ballot(cls == ND_CLASS_SUBWAVE);
+        const uint64_t b_wg = __ballot(cls == ND_CLASS_WORKGROUP);
+        const uint64_t b_grid = __ballot(cls == ND_CLASS_GRID);
+        uint32_t wg_base = 0;
+        if (lane == 0) {
+            if (b_sub) atomicAdd(&ctl->n_sub, (uint32_t)__popcll(b_sub));
+            if (b_wg) wg_base = atomicAdd(&ctl->n_wg, (uint32_t)__popcll(b_wg));
+            if (b_grid) atomicAdd(&ctl->n_grid, (uint32_t)__popcll(b_grid));
+        }
+        wg_base = __shfl(wg_base, 0, 64);
+        if (cls == ND_CLASS_WORKGROUP)
+            list_wg[wg_base + (uint32_t)__popcll(b_wg & lanes_below(lane))] = (int32_t)g;
+        if (b_grid) {  // uniform for the wave
+            const uint32_t chunks = cls == ND_CLASS_GRID
+                                        ? (draws + (uint32_t)sp.wg_max - 1u) / (uint32_t)sp.wg_max
+                                        : 0u;
+            const uint32_t incl = wave_inclusive_scan(chunks, lane);
+            const uint32_t total = __shfl(incl, 63, 64);
+            uint32_t cbase = 0;
+            if (lane == 0) cbase = atomicAdd(&ctl->n_chunks, total);
+            cbase = __shfl(cbase, 0, 64) + incl - chunks;
+            for (uint32_t c = 0; c < chunks; ++c) {
+                if ((int64_t)(cbase + c) < max_chunks) {  // capacity is sized so this always holds
+                    chunk_gid[cbase + c] = (int32_t)g;
+                    chunk_idx[cbase + c] = (int32_t)c;
+                }
+            }
+        }
+    }
+}
+
+}  // namespace
+
+int build_groups(const int32_t* sorted_keys, int64_t max_pairs, StepCtl* ctl, int32_t* g_key,
+                 int32_t* g_start, uint32_t* tile_counts, hipStream_t stream) {
+    int64_t tiles = (max_pairs + kSegTile - 1) / kSegTile;
+    if (tiles < 1) tiles = 1;
+    hipLaunchKernelGGL(seg_count_kernel, dim3((unsigned)tiles), dim3(kSegThreads), 0, stream,
+                       sorted_keys, ctl, tile_counts);
+    hipLaunchKernelGGL(seg_scan_kernel, dim3(1), dim3(1024), 0, stream, tile_counts, tiles, ctl,
+                       g_start);
+    hipLaunchKernelGGL(seg_write_kernel, dim3((unsigned)tiles), dim3(kSegThreads), 0, stream,
+                       sorted_keys, ctl, tile_counts, g_key, g_start);
+    ND_HIP_CHECK(hipGetLastError());
+    return ND_OK;
+}
+
+int classify_groups(const int32_t* g_start, int64_t max_groups, StepCtl* ctl, const SchedParams& sp,
+                    int32_t* list_wg, int32_t* chunk_gid, int32_t* chunk_idx, int64_t max_chunks,
+                    hipStream_t stream) {
+    int64_t blocks = (max_groups + 255) / 256;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(classify_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, g_start, ctl,
+                       sp, list_wg, chunk_gid, chunk_idx, max_chunks);
+    ND_HIP_CHECK(hipGetLastError());
+    return ND_OK;
+}
+
+}  // namespace nd

@@ -1,0 +1,281 @@
+// Grouping (transit, slot) pairs by transit vertex: a stable least-significant-
+// digit radix sort on the transit id, hand-written for gfx950.
+//
+// This is the first stage of the scheduling index of Section 6.1.2 of the
+// paper ("creates a transit-to-sample map"), which Section 8.1 reports as a
+// radix sort of the samples keyed on the transit.  The paper used a vendor
+// sort; here each pass is three kernels:
+//   upsweep    per-tile digit histogram in LDS              (reads 4 B / pair)
+//   binscan    per-digit exclusive scan over the tiles
+//   downsweep  stable in-tile ranking with wave64 ballots, tile-local reorder
+//              in LDS, coalesced scatter                    (reads 8, writes 8 B / pair)
+// The first pass is fused with transit enumeration and output compaction: it
+// reads the previous step's output array directly (the slot index is the
+// implicit value), drops slots without a transit and writes NULL into the
+// children of those slots, so later passes and the sampling kernels only ever
+// see live pairs.
+#include "nd_common.h"
+#include "nd_wave.h"
+
+namespace nd {
+
+SortPlan make_sort_plan(int64_t n_slots, int64_t V) {
+    SortPlan p{};
+    int nbits = 1;
+    while ((1ll << nbits) < V) ++nbits;
+    p.passes = (nbits + kMaxRadixBits - 1) / kMaxRadixBits;
+    int shift = 0;
+    for (int i = 0; i < p.passes; ++i) {
+        p.bits[i] = nbits / p.passes + (i < nbits % p.passes ? 1 : 0);
+        p.shift[i] = shift;
+        shift += p.bits[i];
+    }
+    p.max_tiles = (n_slots + kSortTile - 1) / kSortTile;
+    if (p.max_tiles < 1) p.max_tiles = 1;
+    return p;
+}
+
+size_t sort_hist_bytes(const SortPlan& p) {
+    int maxbits = 0;
+    for (int i = 0; i < p.passes; ++i) maxbits = p.bits[i] > maxbits ? p.bits[i] : maxbits;
+    // per-(digit, tile) counts followed by the per-digit totals
+    return ((size_t)(1 << maxbits) * (size_t)p.max_tiles + 256) * sizeof(uint32_t);
+}
+
+namespace {
+
+constexpr int kWaves = kSortThreads / 64;
+constexpr int kPerWave = kSortTile / kWaves;  // consecutive keys owned by one wave
+
+// FIRST: keys are the raw transit array (negative = no transit), n = n_slots.
+// otherwise: keys are live pairs, n = ctl->P.
+template <bool FIRST>
+__global__ __launch_bounds__(kSortThreads) void upsweep_kernel(
+    const int32_t* __restrict__ keys, int64_t n_slots, const StepCtl* __restrict__ ctl, int shift,
+    int bits, uint32_t* __restrict__ hist, int64_t num_tiles, int32_t V, int check_range,
+    uint32_t* __restrict__ status) {
+    __shared__ uint32_t h[1 << kMaxRadixBits];
+    const int tid = threadIdx.x;
+    const int nbins = 1 << bits;
+    const uint32_t mask = (uint32_t)nbins - 1u;
+    const int64_t n = FIRST ? n_slots : (int64_t)ctl->P;
+    const int64_t base = (int64_t)blockIdx.x * kSortTile;
+    if (tid < nbins) h[tid] = 0;
+    __syncthreads();
+    bool bad = false;
+    if (base < n) {
+#pragma unroll 4
+        for (int i = tid; i < kSortTile; i += kSortThreads) {
+            const int64_t idx = base + i;
+            if (idx < n) {
+                int32_t k = keys[idx];
+                if (FIRST && (k >= V || k < ND_NULL_VERTEX)) {
+                    bad = true;
+                    k = ND_NULL_VERTEX;
+                }
+                if (k >= 0) atomicAdd(&h[((uint32_t)k >> shift) & mask], 1u);
+            }
+        }
+    }
+    if (FIRST && check_range && bad) atomicOr(status, 1u);
+    __syncthreads();
+    if (tid < nbins) hist[(int64_t)tid * num_tiles + blockIdx.x] = h[tid];
+}
+
+// One workgroup per digit value: exclusive scan of that digit's per-tile counts,
+// in place; the digit's total goes to bin_total[digit].
+__global__ __launch_bounds__(256) void binscan_kernel(uint32_t* __restrict__ hist,
+                                                      uint32_t* __restrict__ bin_total,
+                                                      int64_t num_tiles) {
+    __shared__ uint32_t tmp[8];
+    uint32_t* row = hist + (int64_t)blockIdx.x * num_tiles;
+    uint32_t carry = 0;
+    for (int64_t base = 0; base < num_tiles; base += 256) {
+        const int64_t i = base + threadIdx.x;
+        const uint32_t x = i < num_tiles ? row[i] : 0u;
+        uint32_t total;
+        const uint32_t ex = block_exclusive_scan<uint32_t, 256>(x, tmp, &total);
+        if (i < num_tiles) row[i] = carry + ex;
+        carry += total;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) bin_total[blockIdx.x] = carry;
+}
+
+template <bool FIRST>
+__global__ __launch_bounds__(kSortThreads) void downsweep_kernel(
+    const int32_t* __restrict__ keys_in, const int32_t* __restrict__ vals_in, int64_t n_slots,
+    StepCtl* __restrict__ ctl, int shift, int bits, const uint32_t* __restrict__ hist,
+    const uint32_t* __restrict__ bin_total, int64_t num_tiles, int32_t* __restrict__ keys_out,
+    int32_t* __restrict__ vals_out, int32_t* __restrict__ fill_out, int32_t m, int32_t V) {
+    __shared__ uint32_t wave_hist[kWaves][1 << kMaxRadixBits];
+    __shared__ uint32_t digit_start[1 << kMaxRadixBits];
+    __shared__ uint32_t global_base[1 << kMaxRadixBits];
+    __shared__ uint32_t scan_tmp[kWaves + 2];
+    __shared__ int32_t skeys[kSortTile];
+    __shared__ int32_t svals[kSortTile];
+
+    const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
+    const int nbins = 1 << bits;
+    const uint32_t mask = (uint32_t)nbins - 1u;
+    const int64_t n = FIRST ? n_slots : (int64_t)ctl->P;
+    const int64_t base = (int64_t)blockIdx.x * kSortTile;
+
+    // Global start of every digit = exclusive scan of the digit totals; the sum
+    // of the totals is the number of live pairs, which pass 0 publishes.
+    {
+        const uint32_t t = tid < nbins ? bin_total[tid] : 0u;
+        uint32_t total;
+        const uint32_t ex = block_exclusive_scan<uint32_t, kSortThreads>(t, scan_tmp, &total);
+        if (tid < nbins) global_base[tid] = ex + hist[(int64_t)tid * num_tiles + blockIdx.x];
+        if (FIRST && blockIdx.x == 0 && tid == 0) ctl->P = total;
+    }
+    if (base >= n) return;  // uniform for the workgroup
+    for (int i = tid; i < kWaves * (1 << kMaxRadixBits); i += kSortThreads)
+        (&wave_hist[0][0])[i] = 0;
+
+    int32_t key[kSortItems], val[kSortItems];
+    uint32_t rank[kSortItems];
+#pragma unroll
+    for (int r = 0; r < kSortItems; ++r) {
+        const int64_t idx = base + (int64_t)wave * kPerWave + r * 64 + lane;
+        int32_t k = ND_NULL_VERTEX, v = 0;
+        if (idx < n) {
+            k = keys_in[idx];
+            if (FIRST) {
+                if (k >= V || k < 0) k = ND_NULL_VERTEX;
+                v = (int32_t)idx;
+                if (k < 0 && fill_out != nullptr) {
+                    int32_t* dst = fill_out + idx * (int64_t)m;
+                    for (int32_t j = 0; j < m; ++j) dst[j] = ND_NULL_VERTEX;
+                }
+            } else {
+                v = vals_in[idx];
+            }
+        }
+        key[r] = k;
+        val[r] = v;
+    }
+    __syncthreads();
+
+    // Stable rank inside the wave's 1024 consecutive keys: for every group of 64
+    // keys, the lanes holding the same digit are found with one ballot per digit
+    // bit; the lowest such lane advances the wave's running count of the digit.
+#pragma unroll
+    for (int r = 0; r < kSortItems; ++r) {
+        const bool live = key[r] >= 0;
+        const uint32_t d = ((uint32_t)key[r] >> shift) & mask;
+        uint64_t peers = __ballot(live);
+        for (int b = 0; b < bits; ++b) {
+            const bool bit = (d >> b) & 1u;
+            const uint64_t bal = __ballot(live && bit);
+            peers &= bit ? bal : ~bal;
+        }
+        uint32_t old = 0;
+        int leader = lane;
+        if (live) {
+            leader = __ffsll((unsigned long long)peers) - 1;
+            if (lane == leader) {
+                old = wave_hist[wave][d];
+                wave_hist[wave][d] = old + (uint32_t)__popcll(peers);
+            }
+        }
+        // the next group of 64 keys may read this counter from another lane of the wave
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        old = __shfl(old, leader, 64);
+        rank[r] = old + (uint32_t)__popcll(peers & lanes_below(lane));
+    }
+    __syncthreads();
+
+    // Per digit: exclusive scan over the waves (in place) and over the digits.
+    {
+        uint32_t cnt = 0;
+        if (tid < nbins) {
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) {
+                const uint32_t t = wave_hist[w][tid];
+                wave_hist[w][tid] = cnt;
+                cnt += t;
+            }
+        }
+        uint32_t total;
+        const uint32_t ex = block_exclusive_scan<uint32_t, kSortThreads>(cnt, scan_tmp, &total);
+        if (tid < nbins) digit_start[tid] = ex;
+        if (tid == 0) scan_tmp[kWaves + 1] = total;  // live keys of the tile
+    }
+    __syncthreads();
+    const uint32_t tile_live = scan_tmp[kWaves + 1];
+
+#pragma unroll
+    for (int r = 0; r < kSortItems; ++r) {
+        if (key[r] >= 0) {
+            const uint32_t d = ((uint32_t)key[r] >> shift) & mask;
+            const uint32_t pos = digit_start[d] + wave_hist[wave][d] + rank[r];
+            skeys[pos] = key[r];
+            svals[pos] = val[r];
+        }
+    }
+    __syncthreads();
+
+    for (uint32_t i = tid; i < tile_live; i += kSortThreads) {
+        const int32_t k = skeys[i];
+        const uint32_t d = ((uint32_t)k >> shift) & mask;
+        const uint32_t g = global_base[d] + (i - digit_start[d]);
+        keys_out[g] = k;
+        vals_out[g] = svals[i];
+    }
+}
+
+}  // namespace
+
+int sort_pairs(const int32_t* src, int64_t n_slots, int32_t V, const SortPlan& plan, int32_t* keysA,
+               int32_t* valsA, int32_t* keysB, int32_t* valsB, uint32_t* hist, StepCtl* ctl,
+               int32_t* fill_out, int32_t m, uint32_t* status_word, int32_t** keys_out,
+               int32_t** vals_out, hipStream_t stream) {
+    const int64_t tiles = plan.max_tiles;
+    int maxbits = 0;
+    for (int i = 0; i < plan.passes; ++i) maxbits = plan.bits[i] > maxbits ? plan.bits[i] : maxbits;
+    uint32_t* bin_total = hist + (size_t)(1 << maxbits) * (size_t)tiles;
+    const int32_t* kin = src;
+    const int32_t* vin = nullptr;
+    int32_t* kout = keysA;
+    int32_t* vout = valsA;
+    for (int p = 0; p < plan.passes; ++p) {
+        const int bits = plan.bits[p], shift = plan.shift[p];
+        if (p == 0) {
+            hipLaunchKernelGGL(upsweep_kernel<true>, dim3((unsigned)tiles), dim3(kSortThreads), 0,
+                               stream, kin, n_slots, ctl, shift, bits, hist, tiles, V,
+                               status_word != nullptr ? 1 : 0, status_word);
+        } else {
+            hipLaunchKernelGGL(upsweep_kernel<false>, dim3((unsigned)tiles), dim3(kSortThreads), 0,
+                               stream, kin, n_slots, ctl, shift, bits, hist, tiles, V, 0,
+                               (uint32_t*)nullptr);
+        }
+        hipLaunchKernelGGL(binscan_kernel, dim3(1u << bits), dim3(256), 0, stream, hist, bin_total,
+                           tiles);
+        if (p == 0) {
+            hipLaunchKernelGGL(downsweep_kernel<true>, dim3((unsigned)tiles), dim3(kSortThreads), 0,
+                               stream, kin, vin, n_slots, ctl, shift, bits, hist, bin_total, tiles,
+                               kout, vout, fill_out, m, V);
+        } else {
+            hipLaunchKernelGGL(downsweep_kernel<false>, dim3((unsigned)tiles), dim3(kSortThreads), 0,
+                               stream, kin, vin, n_slots, ctl, shift, bits, hist, bin_total, tiles,
+                               kout, vout, (int32_t*)nullptr, m, V);
+        }
+        kin = kout;
+        vin = vout;
+        if (kout == keysA) {
+            kout = keysB;
+            vout = valsB;
+        } else {
+            kout = keysA;
+            vout = valsA;
+        }
+    }
+    ND_HIP_CHECK(hipGetLastError());
+    *keys_out = const_cast<int32_t*>(kin);
+    *vals_out = const_cast<int32_t*>(vin);
+    return ND_OK;
+}
+
+}  // namespace nd

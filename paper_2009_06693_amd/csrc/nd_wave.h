@@ -1,0 +1,48 @@
+// Wave64 and workgroup scan primitives (ballot / shuffle based).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace nd {
+
+__device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & 63); }
+__device__ __forceinline__ int wave_id() { return (int)(threadIdx.x >> 6); }
+
+__device__ __forceinline__ uint64_t lanes_below(int lane) { return (1ull << lane) - 1ull; }
+
+// Inclusive scan across the 64 lanes of a wavefront.
+template <typename T>
+__device__ __forceinline__ T wave_inclusive_scan(T x, int lane) {
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        T y = __shfl_up(x, d, 64);
+        if (lane >= d) x += y;
+    }
+    return x;
+}
+
+// Exclusive scan over a workgroup of THREADS lanes (THREADS a multiple of 64, at
+// most 1024).  `tmp` is shared memory with at least THREADS/64 + 1 entries.
+// Returns the exclusive prefix of x; *total receives the workgroup's sum.
+// Contains two barriers; every thread of the workgroup must call it.
+template <typename T, int THREADS>
+__device__ __forceinline__ T block_exclusive_scan(T x, T* tmp, T* total) {
+    constexpr int W = THREADS / 64;
+    const int lane = lane_id(), wave = wave_id();
+    const T incl = wave_inclusive_scan(x, lane);
+    if (lane == 63) tmp[wave] = incl;
+    __syncthreads();
+    if (wave == 0) {
+        T w = lane < W ? tmp[lane] : (T)0;
+        T wi = wave_inclusive_scan(w, lane);
+        if (lane < W) tmp[lane] = wi - w;
+        if (lane == W - 1) tmp[W] = wi;
+    }
+    __syncthreads();
+    const T base = tmp[wave];
+    *total = tmp[W];
+    return base + incl - x;
+}
+
+}  // namespace nd

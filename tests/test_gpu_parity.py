@@ -1,0 +1,345 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle,
+element by element and bit-exact (vertex ids are integers), on seeded inputs
+that span several sort tiles with a ragged tail."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2009_06693_amd import binding as B
+from paper_2009_06693_amd import inputs
+
+from gpu_util import assert_steps_equal, device_graph, gpu_sample
+
+pytestmark = pytest.mark.gpu
+
+TP, SP = B.ND_MODE_TRANSIT_PARALLEL, B.ND_MODE_SAMPLE_PARALLEL
+
+
+@pytest.fixture(scope="module")
+def small():
+    return inputs.small_graph(10, 12000, seed=11)
+
+
+@pytest.fixture(scope="module")
+def small_w():
+    return inputs.small_graph(10, 12000, seed=12, weighted=True)
+
+
+@pytest.fixture(scope="module")
+def small64():
+    return inputs.small_graph(11, 30000, seed=13, int64_offsets=True)
+
+
+def _roots(g, n, seed):
+    rng = np.random.default_rng(seed)
+    return rng.integers(0, g.V, size=n, dtype=np.int32)
+
+
+# ----------------------------------------------------------------------------- uniform walks
+@pytest.mark.parametrize("mode", [SP, TP])
+@pytest.mark.parametrize("n", [1, 63, 8192, 20011])
+def test_deepwalk_uniform(small, mode, n):
+    dg, og = device_graph(small)
+    roots = _roots(small, n, 1)
+    want = oracle.deepwalk(og, roots, 12, seed=5)
+    got, _ = gpu_sample(dg, B.ND_DEEPWALK, roots, 5, num_steps=12, mode=mode)
+    assert_steps_equal(got, list(want), f"deepwalk mode={mode} n={n}")
+
+
+@pytest.mark.parametrize("force", [B.ND_CLASS_SUBWAVE, B.ND_CLASS_WORKGROUP, B.ND_CLASS_GRID])
+def test_deepwalk_forced_classes(small, force):
+    dg, og = device_graph(small)
+    roots = _roots(small, 9000, 2)
+    want = oracle.deepwalk(og, roots, 6, seed=9)
+    got, stats = gpu_sample(dg, B.ND_DEEPWALK, roots, 9, num_steps=6, sched_force_class=force,
+                            sched_wg_max=64, sched_sub_max=16)
+    assert_steps_equal(got, list(want), f"forced class {force}")
+    col = {B.ND_CLASS_SUBWAVE: 2, B.ND_CLASS_WORKGROUP: 3, B.ND_CLASS_GRID: 4}[force]
+    assert (stats[:, col] == stats[:, 1]).all()          # every transit went to the forced class
+
+
+def test_deepwalk_small_thresholds_use_all_three_classes(small):
+    dg, og = device_graph(small)
+    roots = _roots(small, 30000, 3)
+    want = oracle.deepwalk(og, roots, 8, seed=10)
+    for policy in (0, 1, 2):
+        got, stats = gpu_sample(dg, B.ND_DEEPWALK, roots, 10, num_steps=8, sched_sub_max=4,
+                                sched_wg_max=32, lds_stage_policy=policy)
+        assert_steps_equal(got, list(want), f"three classes, lds policy {policy}")
+        assert (stats[1:, 2] > 0).all() and (stats[1:, 3] > 0).all() and (stats[1:, 4] > 0).all()
+        assert (stats[:, 2] + stats[:, 3] + stats[:, 4] == stats[:, 1]).all()
+        if policy == 1:
+            assert (stats[:, 6] == 0).all()
+        if policy == 2:
+            assert (stats[1:, 6] > 0).all()
+
+
+def test_int64_offsets(small64):
+    dg, og = device_graph(small64)
+    roots = _roots(small64, 12345, 4)
+    want = oracle.deepwalk(og, roots, 7, seed=3)
+    for mode in (SP, TP):
+        got, _ = gpu_sample(dg, B.ND_DEEPWALK, roots, 3, num_steps=7, mode=mode)
+        assert_steps_equal(got, list(want), "int64 offsets")
+
+
+def test_sample_id_base_and_seed(small):
+    dg, og = device_graph(small)
+    roots = _roots(small, 5000, 5)
+    seed = (0xDEADBEEF << 32) | 0x1234567
+    want = oracle.deepwalk(og, roots, 5, seed=seed)
+    got, _ = gpu_sample(dg, B.ND_DEEPWALK, roots[1000:3000], seed, num_steps=5, sample_id_base=1000)
+    assert_steps_equal(got, [w[1000:3000] for w in want], "sample_id_base")
+
+
+# ----------------------------------------------------------------------------- weighted, PPR
+@pytest.mark.parametrize("mode", [SP, TP])
+def test_deepwalk_weighted(small_w, mode):
+    dg, og = device_graph(small_w)
+    roots = _roots(small_w, 20000, 6)
+    want = oracle.deepwalk(og, roots, 10, seed=21, use_weights=True)
+    got, _ = gpu_sample(dg, B.ND_DEEPWALK, roots, 21, num_steps=10, use_weights=1, mode=mode)
+    assert_steps_equal(got, list(want), "weighted deepwalk")
+
+
+def test_weighted_all_classes_and_staging(small_w):
+    dg, og = device_graph(small_w)
+    roots = _roots(small_w, 25000, 7)
+    want = oracle.deepwalk(og, roots, 6, seed=22, use_weights=True)
+    for policy in (1, 2):
+        got, stats = gpu_sample(dg, B.ND_DEEPWALK, roots, 22, num_steps=6, use_weights=1,
+                                sched_sub_max=4, sched_wg_max=32, lds_stage_policy=policy)
+        assert_steps_equal(got, list(want), f"weighted classes policy {policy}")
+        assert (stats[1:, 3] > 0).all() and (stats[1:, 4] > 0).all()
+
+
+@pytest.mark.parametrize("mode", [SP, TP])
+@pytest.mark.parametrize("weighted", [0, 1])
+def test_ppr(small_w, mode, weighted):
+    dg, og = device_graph(small_w)
+    roots = _roots(small_w, 15000, 8)
+    want = oracle.ppr(og, roots, 40, 0.05, seed=31, use_weights=bool(weighted))
+    got, stats = gpu_sample(dg, B.ND_PPR, roots, 31, num_steps=40, term_prob=0.05,
+                            use_weights=weighted, mode=mode)
+    assert_steps_equal(got, list(want), "ppr")
+    if stats is not None:
+        live = stats[:, 0]
+        assert live[0] > live[-1] > 0                      # dead walks are compacted away
+        assert live[1] == (want[0] >= 0).sum()
+
+
+# ----------------------------------------------------------------------------- node2vec
+@pytest.mark.parametrize("mode", [SP, TP])
+@pytest.mark.parametrize("weighted,convention,attempts", [(0, 0, 64), (1, 0, 64), (1, 1, 64),
+                                                          (1, 0, 0), (0, 1, 1), (1, 0, 3)])
+def test_node2vec(small_w, mode, weighted, convention, attempts):
+    dg, og = device_graph(small_w)
+    roots = _roots(small_w, 6000, 9)
+    want = oracle.node2vec(og, roots, 8, 2.0, 0.5, seed=41, use_weights=bool(weighted),
+                           convention=convention, max_attempts=attempts)
+    got, _ = gpu_sample(dg, B.ND_NODE2VEC, roots, 41, num_steps=8, p=2.0, q=0.5,
+                        use_weights=weighted, bias_convention=convention,
+                        n2v_max_attempts=attempts, mode=mode)
+    assert_steps_equal(got, list(want), "node2vec")
+
+
+def test_node2vec_classes(small_w):
+    dg, og = device_graph(small_w)
+    roots = _roots(small_w, 20000, 10)
+    want = oracle.node2vec(og, roots, 5, 0.25, 4.0, seed=43, use_weights=True)
+    for policy in (1, 2):
+        got, stats = gpu_sample(dg, B.ND_NODE2VEC, roots, 43, num_steps=5, p=0.25, q=4.0,
+                                use_weights=1, sched_sub_max=4, sched_wg_max=32,
+                                lds_stage_policy=policy)
+        assert_steps_equal(got, list(want), "node2vec classes")
+        assert (stats[1:, 3] > 0).all() and (stats[1:, 4] > 0).all()
+
+
+# ----------------------------------------------------------------------------- k-hop
+@pytest.mark.parametrize("mode", [SP, TP])
+@pytest.mark.parametrize("fanout", [[25, 10], [3], [2, 3, 4], [1, 1, 1, 1]])
+def test_khop(small, mode, fanout):
+    dg, og = device_graph(small)
+    roots = np.arange(small.V, dtype=np.int32)             # includes isolated vertices
+    want = oracle.khop(og, roots, fanout, seed=51)
+    got, _ = gpu_sample(dg, B.ND_KHOP, roots, 51, num_steps=len(fanout), fanout=fanout, mode=mode)
+    assert_steps_equal(got, want, f"khop {fanout}")
+
+
+@pytest.mark.parametrize("force", [B.ND_CLASS_AUTO, B.ND_CLASS_SUBWAVE, B.ND_CLASS_WORKGROUP,
+                                   B.ND_CLASS_GRID])
+def test_khop_classes(small64, force):
+    dg, og = device_graph(small64)
+    roots = _roots(small64, 3000, 11)
+    want = oracle.khop(og, roots, [7, 5], seed=52)
+    got, stats = gpu_sample(dg, B.ND_KHOP, roots, 52, num_steps=2, fanout=[7, 5],
+                            sched_force_class=force, sched_sub_max=32, sched_wg_max=256)
+    assert_steps_equal(got, want, f"khop forced {force}")
+    if force == B.ND_CLASS_AUTO:
+        assert stats[1, 2] > 0 and stats[1, 3] > 0 and stats[1, 4] > 0
+
+
+def test_khop_split_over_calls(small):
+    dg, og = device_graph(small)
+    roots = _roots(small, 4000, 12)
+    want = oracle.khop(og, roots, [5, 4], seed=53)
+    a, _ = gpu_sample(dg, B.ND_KHOP, roots[:1500], 53, num_steps=2, fanout=[5, 4])
+    b, _ = gpu_sample(dg, B.ND_KHOP, roots[1500:], 53, num_steps=2, fanout=[5, 4], sample_id_base=1500)
+    for i in range(2):
+        assert np.array_equal(np.concatenate([a[i], b[i]]), want[i].reshape(-1))
+
+
+# ----------------------------------------------------------------------------- layer
+@pytest.mark.parametrize("rps,fanout", [(64, [256, 256]), (16, [100]), (1, [7, 300, 5]), (300, [40, 4096])])
+def test_layer(small, rps, fanout):
+    dg, og = device_graph(small)
+    B_ = 37
+    roots = _roots(small, rps * B_, 13)
+    want = oracle.layer(og, roots, rps, fanout, seed=61)
+    got, _ = gpu_sample(dg, B.ND_LAYER, roots, 61, num_steps=len(fanout), fanout=fanout,
+                        roots_per_sample=rps)
+    assert_steps_equal(got, want, f"layer rps={rps} fanout={fanout}")
+
+
+def test_layer_int64_and_base(small64):
+    dg, og = device_graph(small64)
+    roots = inputs.permutation(small64.V, 3)[:32 * 20]
+    want = oracle.layer(og, roots, 32, [128, 128], seed=62)
+    got, _ = gpu_sample(dg, B.ND_LAYER, roots[5 * 32:], 62, num_steps=2, fanout=[128, 128],
+                        roots_per_sample=32, sample_id_base=5)
+    assert_steps_equal(got, [w[5:] for w in want], "layer base")
+
+
+# ----------------------------------------------------------------------------- edge cases
+def test_empty_and_degenerate_inputs(small):
+    dg, og = device_graph(small)
+    got, _ = gpu_sample(dg, B.ND_DEEPWALK, np.zeros(0, dtype=np.int32), 1, num_steps=4)
+    assert all(o.size == 0 for o in got)
+    got, _ = gpu_sample(dg, B.ND_KHOP, np.zeros(0, dtype=np.int32), 1, num_steps=2, fanout=[3, 2])
+    assert all(o.size == 0 for o in got)
+    iso = np.flatnonzero(small.degrees() == 0).astype(np.int32)
+    assert iso.size > 0
+    for mode in (SP, TP):
+        got, _ = gpu_sample(dg, B.ND_KHOP, iso, 1, num_steps=2, fanout=[3, 2], mode=mode)
+        assert all((o == -1).all() for o in got)
+        got, _ = gpu_sample(dg, B.ND_DEEPWALK, iso[:1], 1, num_steps=3, mode=mode)
+        assert all((o == -1).all() for o in got)
+
+
+def test_all_walks_on_one_vertex(small):
+    # one transit with thousands of samples: the grid class with many chunks
+    dg, og = device_graph(small)
+    hub = int(np.argmax(small.degrees()))
+    roots = np.full(70000, hub, dtype=np.int32)
+    want = oracle.khop(og, roots, [3, 2], seed=71)
+    got, stats = gpu_sample(dg, B.ND_KHOP, roots, 71, num_steps=2, fanout=[3, 2])
+    assert_steps_equal(got, want, "single hub")
+    assert stats[0, 1] == 1 and stats[0, 4] == 1 and stats[0, 5] == -(-70000 * 3 // 8192)
+
+
+def test_bad_roots_are_null_and_reported(small):
+    dg, og = device_graph(small)
+    roots = _roots(small, 3000, 14)
+    roots[[5, 77, 2999]] = [small.V, -7, 2 ** 31 - 1]
+    want = oracle.deepwalk(og, roots, 4, seed=81)
+    for mode in (SP, TP):
+        got, _ = gpu_sample(dg, B.ND_DEEPWALK, roots, 81, check_status=False, num_steps=4, mode=mode)
+        assert_steps_equal(got, list(want), "bad roots")
+        p = B.nd_params_init(num_steps=4, mode=mode)
+        s = B.Sampler(dg, B.ND_DEEPWALK, p, roots.size)
+        s.run(torch.as_tensor(roots, device="cuda:0"), 81)
+        with pytest.raises(B.NdError) as e:
+            s.status()
+        assert e.value.code == B.ND_ERR_BAD_ROOT
+    roots[[5, 77, 2999]] = -1                                # -1 is a legal "no root"
+    got, _ = gpu_sample(dg, B.ND_DEEPWALK, roots, 81, num_steps=4)
+    assert_steps_equal(got, list(want), "null roots")
+
+
+def test_repeated_runs_are_identical(small):
+    dg, og = device_graph(small)
+    roots = _roots(small, 10000, 15)
+    a, _ = gpu_sample(dg, B.ND_KHOP, roots, 91, num_steps=2, fanout=[6, 3])
+    b, _ = gpu_sample(dg, B.ND_KHOP, roots, 91, num_steps=2, fanout=[6, 3])
+    assert all(np.array_equal(x, y) for x, y in zip(a, b))
+
+
+def test_device_resident_graph_source(small_w):
+    g = small_w
+    dg = B.nd_graph_create(torch.as_tensor(g.row_offsets, device="cuda:0"),
+                           torch.as_tensor(g.col_indices, device="cuda:0"),
+                           torch.as_tensor(g.weights, device="cuda:0"))
+    _, og = device_graph(g)
+    roots = _roots(g, 4000, 16)
+    want = oracle.deepwalk(og, roots, 5, seed=95, use_weights=True)
+    got, _ = gpu_sample(dg, B.ND_DEEPWALK, roots, 95, num_steps=5, use_weights=1)
+    assert_steps_equal(got, list(want), "device source")
+
+
+# ----------------------------------------------------------------------------- grouping on its own
+@pytest.mark.parametrize("n,V", [(0, 10), (1, 1), (100, 3), (8192, 300), (8193, 70000),
+                                 (200001, 1 << 22), (50000, 2)])
+def test_group_by_transit_matches_stable_sort(n, V):
+    rng = np.random.default_rng(n + V)
+    t = rng.integers(0, V, size=n, dtype=np.int32)
+    if n > 10:
+        t[rng.integers(0, n, size=n // 7)] = -1             # dead slots
+        t[rng.integers(0, n, size=n // 5)] = t[0] if t[0] >= 0 else 0   # a heavy transit
+    sk, sv, gk, gs, P, U = B.nd_group_by_transit(torch.as_tensor(t, device="cuda:0"), V)
+    live = np.flatnonzero(t >= 0)
+    order = live[np.argsort(t[live], kind="stable")]
+    assert P == live.size
+    assert np.array_equal(sv.cpu().numpy(), order.astype(np.int32))
+    assert np.array_equal(sk.cpu().numpy(), t[order])
+    uniq, first = np.unique(t[order], return_index=True)
+    assert U == uniq.size
+    assert np.array_equal(gk.cpu().numpy(), uniq)
+    assert np.array_equal(gs.cpu().numpy(), np.append(first, P).astype(np.int32))
+
+
+# ----------------------------------------------------------------------------- loader errors
+def test_graph_validation_errors():
+    off = np.array([0, 2, 3], dtype=np.int32)
+    col = np.array([0, 1, 0], dtype=np.int32)
+    B.nd_graph_create(off, col).destroy()
+    cases = [
+        (np.array([1, 2, 3], dtype=np.int32), col, None, B.ND_ERR_BAD_GRAPH),
+        (np.array([0, 3, 2], dtype=np.int32), col, None, B.ND_ERR_BAD_GRAPH),
+        (np.array([0, 2, 2], dtype=np.int32), col, None, B.ND_ERR_BAD_GRAPH),
+        (off, np.array([0, 2, 0], dtype=np.int32), None, B.ND_ERR_BAD_GRAPH),
+        (off, np.array([1, 0, 0], dtype=np.int32), None, B.ND_ERR_BAD_GRAPH),
+        (off, np.array([1, 1, 0], dtype=np.int32), None, B.ND_ERR_BAD_GRAPH),
+        (off, col, np.array([1.0, -1.0, 2.0], dtype=np.float32), B.ND_ERR_BAD_WEIGHT),
+        (off, col, np.array([1.0, np.nan, 2.0], dtype=np.float32), B.ND_ERR_BAD_WEIGHT),
+        (off, col, np.array([1.0, 40000.0, 2.0], dtype=np.float32), B.ND_ERR_BAD_WEIGHT),
+    ]
+    for o, c, w, code in cases:
+        with pytest.raises(B.NdError) as e:
+            B.nd_graph_create(o, c, w)
+        assert e.value.code == code
+
+
+def test_argument_errors(small):
+    dg, _ = device_graph(small)
+    r = torch.zeros(8, dtype=torch.int32, device="cuda:0")
+    for app, kw, code in [
+        (B.ND_DEEPWALK, dict(num_steps=3, use_weights=1), B.ND_ERR_NO_WEIGHTS),
+        (B.ND_DEEPWALK, dict(num_steps=0), B.ND_ERR_BAD_ARGUMENT),
+        (B.ND_KHOP, dict(num_steps=2, fanout=[3, 0]), B.ND_ERR_BAD_ARGUMENT),
+        (B.ND_LAYER, dict(num_steps=1, fanout=[4], roots_per_sample=3), B.ND_ERR_BAD_ARGUMENT),
+        (B.ND_NODE2VEC, dict(num_steps=2, p=1e-9), B.ND_ERR_BAD_ARGUMENT),
+        (B.ND_PPR, dict(num_steps=2, term_prob=1.5), B.ND_ERR_BAD_ARGUMENT),
+        (B.ND_DEEPWALK, dict(num_steps=2, sample_id_base=2 ** 32 - 4), B.ND_ERR_TOO_LARGE),
+        (7, dict(num_steps=2), B.ND_ERR_BAD_ARGUMENT),
+    ]:
+        p = B.nd_params_init(**kw)
+        with pytest.raises(B.NdError) as e:
+            s = B.Sampler(dg, app, p, 8)
+            s.run(r, 1)
+        assert e.value.code == code, (app, kw)
+    p = B.nd_params_init(num_steps=3)
+    s = B.Sampler(dg, B.ND_DEEPWALK, p, 8)
+    with pytest.raises(B.NdError) as e:
+        B.nd_sample(dg, B.ND_DEEPWALK, p, r, 1, s.out, s.workspace[:256])
+    assert e.value.code == B.ND_ERR_WORKSPACE
