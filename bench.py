@@ -1,0 +1,206 @@
+#!/usr/bin/env python3
+"""Benchmark of the transit-parallel sampling path on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic input:
+one nd_sample call (transit enumeration, radix sort by transit, segmented scan,
+classification, the three class kernels, output compaction) over every root of
+the workload.  Inputs are resident in HBM before the timed region.  Prints one
+JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--mode tp|sp]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+# Integer issue rate of the chip: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz.  A full-rate
+# 32-bit integer instruction occupies one lane-slot, a 32x32->64 multiply four.
+ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+# Algorithmic lane-slots of one uniform draw: Philox4x32-10 is 20 widening multiplies
+# (4 slots each) and 40 XORs; the index is one more multiply-high; 6 slots of addressing.
+ALU_SLOTS_PER_UNIFORM_DRAW = 20 * 4 + 40 + 4 + 6
+
+WORKLOADS = {
+    # name: (graph builder, app, params, description)
+    "c5_khop": ("config5_graph", "khop", dict(num_steps=2, fanout=[25, 10]),
+                "k-hop [25,10], every vertex a root, R-MAT scale 22 (int64 offsets)"),
+    "c5_deepwalk": ("config5_graph", "deepwalk", dict(num_steps=100),
+                    "DeepWalk length 100, one walk per vertex, R-MAT scale 22"),
+    "c3_khop": ("config3_graph", "khop", dict(num_steps=2, fanout=[25, 10]),
+                "k-hop [25,10], every vertex a root (228 batches of 1,024 in one call), 233K dense"),
+    "c2_node2vec": ("config2_graph", "node2vec", dict(num_steps=100, p=2.0, q=0.5, use_weights=1),
+                    "node2vec p=2 q=0.5 length 100, 57K power-law, weights U[1,5)"),
+    "c2_ppr": ("config2_graph", "ppr", dict(num_steps=100, term_prob=0.01, use_weights=1),
+               "PPR termination 0.01 cap 100, 57K power-law, weights U[1,5)"),
+    "c1_deepwalk": ("config1_graph", "deepwalk", dict(num_steps=100),
+                    "DeepWalk length 100, R-MAT scale 12"),
+    "c4_layer": ("config4_graph", "layer", dict(num_steps=2, fanout=[2048, 2048], roots_per_sample=64),
+                 "layer sampling 64 roots, 2 x 2,048, 4,096 batches, 3M power-law"),
+}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c5_khop", choices=sorted(WORKLOADS))
+    ap.add_argument("--mode", default="tp", choices=["tp", "sp"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--sub-max", type=int, default=0)
+    ap.add_argument("--wg-max", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only; sampling shards by samples with the "
+              "graph replicated, which one GPU cannot show (use --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2009_06693_amd import binding as B
+    from paper_2009_06693_amd import inputs
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    builder, app_name, pkw, desc = WORKLOADS[args.workload]
+    app = {"deepwalk": B.ND_DEEPWALK, "ppr": B.ND_PPR, "node2vec": B.ND_NODE2VEC, "khop": B.ND_KHOP,
+           "layer": B.ND_LAYER}[app_name]
+    t0 = time.time()
+    g = getattr(inputs, builder)()
+    sys.stderr.write(f"[bench] {g.describe()} (generated in {time.time() - t0:.1f}s)\n")
+    dg = B.nd_graph_create(g.row_offsets, g.col_indices, g.weights)
+    if app == B.ND_LAYER:
+        roots_np = inputs.permutation(g.V, 4)[:4096 * 64].copy()
+    else:
+        roots_np = np.arange(g.V, dtype=np.int32)
+    roots = torch.as_tensor(roots_np, device="cuda:0")
+    mode = B.ND_MODE_TRANSIT_PARALLEL if args.mode == "tp" else B.ND_MODE_SAMPLE_PARALLEL
+    p = B.nd_params_init(mode=mode, sched_sub_max=args.sub_max, sched_wg_max=args.wg_max, **pkw)
+    s = B.Sampler(dg, app, p, int(roots.numel()))
+    seed = 1
+
+    for _ in range(args.warmup):
+        s.run(roots, seed)
+    torch.cuda.synchronize()
+    s.status()
+
+    # Timed region: K whole nd_sample calls, bracketed by events on the launch stream.
+    # Phase marks (HIP events inside the library) give the per-kernel durations of the
+    # same region.
+    B.nd_profile_enable(True)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(args.steps):
+        out = s.run(roots, seed)
+    e1.record()
+    torch.cuda.synchronize()
+    ms_total = e0.elapsed_time(e1)
+    phases = B.nd_profile_read()
+    B.nd_profile_enable(False)
+    ms_per_step = ms_total / args.steps
+
+    slots = int(sum(s.step_len))
+    live = int(sum(int((o >= 0).sum()) for o in out))
+    value = live / (ms_per_step * 1e-3)
+
+    # ---- roofline of the dominant kernel (the phase with the largest share that is one launch)
+    stats = s.stats() if (mode == B.ND_MODE_TRANSIT_PARALLEL and app != B.ND_LAYER) else None
+    phase_ms = {k: v[0] / args.steps for k, v in phases.items() if v[1] > 0}
+    launches = {k: v[1] / args.steps for k, v in phases.items() if v[1] > 0}
+    kernel_phases = [k for k in ("sample_sub", "sample_sp", "layer", "sample_wg", "sample_grid") if k in phase_ms]
+    dom = max(kernel_phases, key=lambda k: phase_ms[k])
+    avg_launch_ms = phase_ms[dom] / launches[dom]
+    if stats is not None and dom == "sample_sub":
+        # draws of the sub-wavefront class per launch: all live pairs x m minus what the heavy
+        # classes took is not tracked per draw, so count every live pair (upper bound on work
+        # skipped is the heavy classes' share, reported separately below)
+        m_per_step = [pkw.get("fanout", [1] * len(s.step_len))[i] if app == B.ND_KHOP else 1
+                      for i in range(len(s.step_len))]
+        draws = sum(int(stats[i, 0]) * m_per_step[i] for i in range(len(s.step_len)))
+    else:
+        draws = live if dom != "sample_sp" else slots
+    draws_per_launch = draws / launches[dom]
+    hbm_bytes_per_draw = 8.0 if app != B.ND_KHOP else (4.0 + 4.0 + 8.0 / 10.0)
+    hbm_gbs = draws_per_launch * hbm_bytes_per_draw / (avg_launch_ms * 1e-3) / 1e9
+    alu_tops = draws_per_launch * ALU_SLOTS_PER_UNIFORM_DRAW / (avg_launch_ms * 1e-3) / 1e12
+    roofline = {
+        "kernel": {"sample_sub": "sample_sub_kernel", "sample_sp": "sample_sp_kernel",
+                   "layer": "layer_kernel", "sample_wg": "sample_wg_kernel<.., false>",
+                   "sample_grid": "sample_wg_kernel<.., true>"}[dom],
+        "bound": "alu", "achieved": round(alu_tops, 3), "peak": round(ALU_PEAK_TOPS, 3),
+        "unit": "Tslot/s", "frac": round(alu_tops / ALU_PEAK_TOPS, 4),
+        "traffic": None,
+        "avg_launch_ms": round(avg_launch_ms, 4), "launches_per_step": launches[dom],
+        "draws_per_launch": int(draws_per_launch),
+        "hbm_view": {"achieved": round(hbm_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(hbm_gbs / HBM_PEAK_GBS, 4),
+                     "algorithmic_bytes_per_draw": hbm_bytes_per_draw},
+    }
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        import oracle
+        og = oracle.OracleGraph(g.row_offsets, g.col_indices, g.weights)
+
+        def run_oracle(n):
+            r = roots_np[:n]
+            t = time.perf_counter()
+            if app == B.ND_KHOP:
+                o = oracle.khop(og, r, pkw["fanout"], seed)
+            elif app == B.ND_DEEPWALK:
+                o = list(oracle.deepwalk(og, r, pkw["num_steps"], seed, use_weights=bool(pkw.get("use_weights", 0))))
+            elif app == B.ND_PPR:
+                o = list(oracle.ppr(og, r, pkw["num_steps"], pkw["term_prob"], seed, use_weights=bool(pkw.get("use_weights", 0))))
+            elif app == B.ND_NODE2VEC:
+                o = list(oracle.node2vec(og, r, pkw["num_steps"], pkw["p"], pkw["q"], seed, use_weights=bool(pkw.get("use_weights", 0))))
+            else:
+                o = oracle.layer(og, r, pkw["roots_per_sample"], pkw["fanout"], seed)
+            dt = time.perf_counter() - t
+            return sum(int((x >= 0).sum()) for x in o), dt, o
+
+        unit = pkw.get("roots_per_sample", 1)
+        n_probe = min(int(roots_np.size), 2048 * unit if app != B.ND_LAYER else 2 * unit)
+        live_probe, dt_probe, o_probe = run_oracle(n_probe)
+        # the probe doubles as a parity spot-check of this very run
+        for i, x in enumerate(o_probe):
+            got = out[i][: x.size].cpu().numpy()
+            assert np.array_equal(got, np.asarray(x).reshape(-1)), f"GPU and oracle differ at step {i}"
+        n = int(min(roots_np.size, max(n_probe, n_probe * args.cpu_seconds / max(dt_probe, 1e-6))))
+        n -= n % unit
+        live_cpu, dt_cpu, _ = run_oracle(n)
+        cpu_baseline = {"value": round(live_cpu / dt_cpu, 1), "unit": "sampled vertices/s", "cores": 1,
+                        "kind": "oracle",
+                        "sample": f"first {n} of {roots_np.size} roots of the same workload, "
+                                  f"{dt_cpu:.1f} s of single-threaded oracle time"}
+
+    line = {
+        "metric": "sampled vertices/sec per step-batch on 1 MI355X; achieved HBM GB/s vs peak",
+        "value": round(value, 1), "unit": "sampled vertices/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "int32", "data": "synthetic",
+        "config": {"workload": args.workload, "description": desc, "mode": args.mode,
+                   "graph": g.describe(), "roots": int(roots.numel()), "seed": seed,
+                   "slots_per_step": slots, "non_null_per_step": live},
+        "slots_per_s": round(slots / (ms_per_step * 1e-3), 1),
+        "phase_ms_per_step": {k: round(v, 4) for k, v in phase_ms.items()},
+        "roofline": roofline, "cpu_baseline": cpu_baseline,
+    }
+    if stats is not None:
+        line["scheduling"] = {"live_pairs": [int(x) for x in stats[:2, 0]] + ([int(stats[-1, 0])] if len(stats) > 2 else []),
+                              "distinct_transits": [int(x) for x in stats[:2, 1]],
+                              "sub_wg_grid": [[int(x) for x in stats[i, 2:5]] for i in range(min(2, len(stats)))]}
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

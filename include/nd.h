@@ -224,6 +224,34 @@ int nd_group_by_transit(const int32_t* transits_dev, int64_t n, int64_t V,
                         int32_t* group_transit_dev, int32_t* group_start_dev, int64_t* counts_dev,
                         void* workspace_dev, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Phase timing, for measurement.  After nd_profile_enable(1) on a thread, the
+ * nd_sample calls of that thread bracket every phase of every step with HIP
+ * events on their stream (a few microseconds per step; no synchronisation).
+ * nd_profile_read waits for the recorded events, adds the elapsed milliseconds
+ * and the number of intervals of every phase since the previous read to
+ * ms[ND_PHASE_COUNT] and intervals[ND_PHASE_COUNT] (the caller zeroes them),
+ * and resets the recording.  At most 16384 events are kept between reads;
+ * later marks are dropped and nd_profile_read then returns ND_ERR_BAD_ARGUMENT.
+ * The sub-wavefront, workgroup and grid phases each contain exactly one kernel
+ * launch per step.
+ */
+typedef enum nd_phase {
+    ND_PHASE_NONE = -1,
+    ND_PHASE_INIT = 0,        /* workspace header / bitmap reset                    */
+    ND_PHASE_FILL = 1,        /* NULL children of slots without a transit           */
+    ND_PHASE_SORT = 2,        /* transit enumeration + radix sort by transit        */
+    ND_PHASE_GROUP = 3,       /* segmented scan + classification                    */
+    ND_PHASE_SAMPLE_SUB = 4,  /* sub-wavefront class kernel                         */
+    ND_PHASE_SAMPLE_WG = 5,   /* workgroup class kernel                             */
+    ND_PHASE_SAMPLE_GRID = 6, /* grid class kernel                                  */
+    ND_PHASE_SAMPLE_SP = 7,   /* sample-parallel kernel (ablation mode)             */
+    ND_PHASE_LAYER = 8,       /* collective (layer) kernel                          */
+    ND_PHASE_COUNT = 9
+} nd_phase;
+int nd_profile_enable(int on);
+int nd_profile_read(double* ms, int64_t* intervals);
+
 const char* nd_last_error(void);
 int nd_version(void);
 

@@ -30,7 +30,10 @@ ND_ERR_NO_WEIGHTS, ND_ERR_WORKSPACE, ND_ERR_HIP, ND_ERR_BAD_ROOT, ND_ERR_TOO_LAR
 
 EXPORTS = ["nd_params_init", "nd_graph_create", "nd_graph_destroy", "nd_graph_info", "nd_sample_query",
            "nd_sample", "nd_sample_status", "nd_sample_stats", "nd_group_workspace_bytes",
-           "nd_group_by_transit", "nd_last_error", "nd_version"]
+           "nd_group_by_transit", "nd_profile_enable", "nd_profile_read", "nd_last_error", "nd_version"]
+
+ND_PHASES = ["init", "fill", "sort", "group", "sample_sub", "sample_wg", "sample_grid", "sample_sp",
+             "layer"]
 
 
 class nd_params(ctypes.Structure):
@@ -99,6 +102,10 @@ def lib() -> ctypes.CDLL:
         L.nd_group_workspace_bytes.argtypes = [i64, i64]
         L.nd_group_by_transit.restype = ctypes.c_int
         L.nd_group_by_transit.argtypes = [vp, i64, i64, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.nd_profile_enable.restype = ctypes.c_int
+        L.nd_profile_enable.argtypes = [ctypes.c_int]
+        L.nd_profile_read.restype = ctypes.c_int
+        L.nd_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
         L.nd_last_error.restype = ctypes.c_char_p
         L.nd_last_error.argtypes = []
         L.nd_version.restype = ctypes.c_int
@@ -229,6 +236,19 @@ def nd_sample_stats(workspace: torch.Tensor, num_steps: int, stream=None) -> np.
     out = (ctypes.c_int64 * (8 * num_steps))()
     _check(lib().nd_sample_stats(workspace.data_ptr(), _stream_ptr(stream), num_steps, out))
     return np.array(out, dtype=np.int64).reshape(num_steps, 8)
+
+
+def nd_profile_enable(on: bool):
+    _check(lib().nd_profile_enable(int(on)))
+
+
+def nd_profile_read():
+    """Returns {phase: (milliseconds, intervals)} accumulated since the previous read."""
+    n = len(ND_PHASES)
+    ms = (ctypes.c_double * n)()
+    cnt = (ctypes.c_int64 * n)()
+    _check(lib().nd_profile_read(ms, cnt))
+    return {ND_PHASES[i]: (float(ms[i]), int(cnt[i])) for i in range(n)}
 
 
 def nd_group_by_transit(transits: torch.Tensor, V: int, stream=None):

@@ -7,6 +7,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <vector>
 
 #include "nd_common.h"
 #include "nd_sample.h"
@@ -34,7 +35,9 @@ struct Plan {
     int64_t cap_wg = 0, cap_chunks = 0;
     // workspace offsets
     size_t o_ctl = 0, o_keysA = 0, o_valsA = 0, o_keysB = 0, o_valsB = 0, o_hist = 0, o_tiles = 0,
-           o_gkey = 0, o_gstart = 0, o_list_wg = 0, o_chunk_gid = 0, o_chunk_idx = 0, total = 0;
+           o_gkey = 0, o_gstart = 0, o_list_wg = 0, o_chunk_gid = 0, o_chunk_idx = 0, o_bits = 0,
+           total = 0;
+    int64_t bit_words = 0;
 };
 
 int64_t step_fanout(int app, const nd_params* p, int i) {
@@ -96,8 +99,8 @@ int check_params(const Graph& g, int app, const nd_params* p, int64_t num_roots,
     pl->mode = p->mode;
     pl->k = p->num_steps;
     pl->collective = app == ND_LAYER;
-    pl->sub_max = p->sched_sub_max ? p->sched_sub_max : 64;
-    pl->wg_max = p->sched_wg_max ? p->sched_wg_max : 8192;
+    pl->sub_max = p->sched_sub_max ? p->sched_sub_max : 16384;
+    pl->wg_max = p->sched_wg_max ? p->sched_wg_max : 65536;
     if (pl->wg_max < pl->sub_max) {
         set_error("sched_wg_max below sched_sub_max");
         return ND_ERR_BAD_ARGUMENT;
@@ -197,17 +200,21 @@ void layout(Plan* pl, int64_t V) {
         pl->o_list_wg = o; o = align_up(o + (size_t)pl->cap_wg * 4);
         pl->o_chunk_gid = o; o = align_up(o + (size_t)pl->cap_chunks * 4);
         pl->o_chunk_idx = o; o = align_up(o + (size_t)pl->cap_chunks * 4);
+        pl->bit_words = (V + 31) / 32;
+        pl->o_bits = o; o = align_up(o + (size_t)pl->bit_words * 4);
     }
     pl->total = o;
 }
 
-__global__ void init_header_kernel(WsHeader* h, uint32_t num_steps, StepCtl* ctl) {
-    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+__global__ void init_header_kernel(WsHeader* h, uint32_t num_steps, StepCtl* ctl, uint32_t* bits,
+                                   int64_t bit_words) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i == 0) {
         h->status = 0;
         h->num_steps = num_steps;
     }
-    if (i < num_steps) ctl[i] = StepCtl{0, 0, 0, 0, 0, 0, 0, 0};
+    if (i < num_steps) ctl[i] = StepCtl{};
+    if (i < bit_words) bits[i] = 0;
 }
 
 __global__ void publish_counts_kernel(const StepCtl* ctl, int64_t* counts) {
@@ -223,6 +230,30 @@ uint32_t q16(double x) {
 
 }  // namespace
 
+namespace {
+struct Profiler {
+    bool on = false;
+    bool overflow = false;
+    std::vector<hipEvent_t> events;   // pool, created on enable
+    std::vector<int> phase;           // phase that starts at event i
+    size_t used = 0;
+};
+thread_local Profiler g_prof;
+constexpr size_t kMaxEvents = 16384;
+}  // namespace
+
+void mark_phase(int phase, hipStream_t stream) {
+    Profiler& p = g_prof;
+    if (!p.on) return;
+    if (p.used >= p.events.size()) {
+        p.overflow = true;
+        return;
+    }
+    if (hipEventRecord(p.events[p.used], stream) != hipSuccess) return;
+    p.phase[p.used] = phase;
+    ++p.used;
+}
+
 void set_error(const char* fmt, ...) {
     va_list ap;
     va_start(ap, fmt);
@@ -237,6 +268,53 @@ using namespace nd;
 extern "C" {
 
 const char* nd_last_error(void) { return g_error; }
+
+int nd_profile_enable(int on) {
+    Profiler& p = g_prof;
+    if (on && p.events.empty()) {
+        p.events.resize(kMaxEvents);
+        p.phase.assign(kMaxEvents, ND_PHASE_NONE);
+        for (size_t i = 0; i < kMaxEvents; ++i) ND_HIP_CHECK(hipEventCreate(&p.events[i]));
+    }
+    if (!on && !p.events.empty()) {
+        for (hipEvent_t e : p.events) (void)hipEventDestroy(e);
+        p.events.clear();
+        p.phase.clear();
+    }
+    p.on = on != 0;
+    p.used = 0;
+    p.overflow = false;
+    return ND_OK;
+}
+
+int nd_profile_read(double* ms, int64_t* intervals) {
+    Profiler& p = g_prof;
+    if (!ms || !intervals) {
+        set_error("ms or intervals is NULL");
+        return ND_ERR_NULL_POINTER;
+    }
+    if (!p.on) {
+        set_error("profiling is not enabled on this thread");
+        return ND_ERR_BAD_ARGUMENT;
+    }
+    if (p.used > 0) ND_HIP_CHECK(hipEventSynchronize(p.events[p.used - 1]));
+    for (size_t i = 0; i + 1 < p.used; ++i) {
+        const int ph = p.phase[i];
+        if (ph < 0 || ph >= ND_PHASE_COUNT) continue;
+        float t = 0.f;
+        ND_HIP_CHECK(hipEventElapsedTime(&t, p.events[i], p.events[i + 1]));
+        ms[ph] += (double)t;
+        intervals[ph] += 1;
+    }
+    const bool overflow = p.overflow;
+    p.used = 0;
+    p.overflow = false;
+    if (overflow) {
+        set_error("more than %zu phase marks between two reads; the rest were dropped", kMaxEvents);
+        return ND_ERR_BAD_ARGUMENT;
+    }
+    return ND_OK;
+}
 int nd_version(void) { return ND_VERSION; }
 
 void nd_params_init(nd_params* p) {
@@ -351,10 +429,17 @@ int nd_sample(const nd_graph* h, int app, const nd_params* params, const int32_t
     char* ws = (char*)workspace_dev;
     WsHeader* hdr = (WsHeader*)ws;
     StepCtl* ctl = (StepCtl*)(ws + pl.o_ctl);
-    hipLaunchKernelGGL(init_header_kernel, dim3((unsigned)((pl.k + 255) / 256)), dim3(256), 0, stream,
-                       hdr, (uint32_t)pl.k, ctl);
+    mark_phase(ND_PHASE_INIT, stream);
+    {
+        const int64_t n_init = pl.bit_words > pl.k ? pl.bit_words : pl.k;
+        hipLaunchKernelGGL(init_header_kernel, dim3((unsigned)((n_init + 255) / 256)), dim3(256), 0,
+                           stream, hdr, (uint32_t)pl.k, ctl, (uint32_t*)(ws + pl.o_bits), pl.bit_words);
+    }
     ND_HIP_CHECK(hipGetLastError());
-    if (pl.S == 0) return ND_OK;
+    if (pl.S == 0) {
+        mark_phase(ND_PHASE_NONE, stream);
+        return ND_OK;
+    }
 
     if (app == ND_LAYER) {
         for (int i = 0; i < pl.k; ++i) {
@@ -368,9 +453,11 @@ int nd_sample(const nd_graph* h, int app, const nd_params* params, const int32_t
             a.out = step_out_dev[i];
             a.check_roots = i == 0;
             a.status = &hdr->status;
+            mark_phase(ND_PHASE_LAYER, stream);
             rc = layer_step(g, a, pl.S, stream);
             if (rc != ND_OK) return rc;
         }
+        mark_phase(ND_PHASE_NONE, stream);
         return ND_OK;
     }
 
@@ -416,6 +503,7 @@ int nd_sample(const nd_graph* h, int app, const nd_params* params, const int32_t
         a.prev_transit = i == 0 ? nullptr : (i == 1 ? roots_dev : step_out_dev[i - 2]);
         a.out = step_out_dev[i];
         if (pl.mode == ND_MODE_SAMPLE_PARALLEL) {
+            mark_phase(ND_PHASE_SAMPLE_SP, stream);
             rc = sample_step_sp(g, draw, a, src, n_slots, i == 0, &hdr->status, stream);
             if (rc != ND_OK) return rc;
             continue;
@@ -423,20 +511,31 @@ int nd_sample(const nd_graph* h, int app, const nd_params* params, const int32_t
         SchedParams sp{m, pl.sub_max, pl.wg_max, params->sched_force_class};
         const SortPlan plan = make_sort_plan(n_slots, g.V);
         int32_t *keys = nullptr, *vals = nullptr;
+        // children of slots without a transit: the first sort pass writes them for m <= 2,
+        // a flat fill kernel (contiguous stores) otherwise
+        if (m > 2) {
+            mark_phase(ND_PHASE_FILL, stream);
+            rc = fill_dead_children(g, src, n_slots, m, step_out_dev[i], stream);
+            if (rc != ND_OK) return rc;
+        }
+        mark_phase(ND_PHASE_SORT, stream);
         rc = sort_pairs(src, n_slots, (int32_t)g.V, plan, (int32_t*)(ws + pl.o_keysA),
                         (int32_t*)(ws + pl.o_valsA), (int32_t*)(ws + pl.o_keysB),
                         (int32_t*)(ws + pl.o_valsB), (uint32_t*)(ws + pl.o_hist), ctl + i,
-                        step_out_dev[i], m, i == 0 ? &hdr->status : nullptr, &keys, &vals, stream);
+                        m > 2 ? nullptr : step_out_dev[i], m, i == 0 ? &hdr->status : nullptr, &keys,
+                        &vals, stream);
         if (rc != ND_OK) return rc;
         int32_t* g_key = (int32_t*)(ws + pl.o_gkey);
         int32_t* g_start = (int32_t*)(ws + pl.o_gstart);
+        mark_phase(ND_PHASE_GROUP, stream);
         rc = build_groups(keys, n_slots, ctl + i, g_key, g_start, (uint32_t*)(ws + pl.o_tiles), stream);
         if (rc != ND_OK) return rc;
         int32_t* list_wg = (int32_t*)(ws + pl.o_list_wg);
         int32_t* chunk_gid = (int32_t*)(ws + pl.o_chunk_gid);
         int32_t* chunk_idx = (int32_t*)(ws + pl.o_chunk_idx);
-        rc = classify_groups(g_start, n_slots, ctl + i, sp, list_wg, chunk_gid, chunk_idx,
-                             pl.cap_chunks, stream);
+        uint32_t* heavy_bits = sp.force_class == ND_CLASS_AUTO ? (uint32_t*)(ws + pl.o_bits) : nullptr;
+        rc = classify_groups(g_key, g_start, n_slots, ctl + i, sp, list_wg, chunk_gid, chunk_idx,
+                             pl.cap_chunks, heavy_bits, stream);
         if (rc != ND_OK) return rc;
         // work-list bounds for this step's launch shapes
         int64_t max_wg = n_out / pl.sub_max + 1;
@@ -446,11 +545,25 @@ int nd_sample(const nd_graph* h, int app, const nd_params* params, const int32_t
             max_chunks += n_slots;
         }
         if (max_wg > n_slots) max_wg = n_slots;
-        rc = sample_step_tp(g, draw, a, sp, ctl + i, g_key, g_start, vals, list_wg, chunk_gid,
-                            chunk_idx, n_slots, max_wg, max_chunks, pl.cap_wg, pl.cap_chunks,
-                            g.num_cus, stream);
+        TpStep t{};
+        t.ctl = ctl + i;
+        t.keys = keys;
+        t.vals = vals;
+        t.g_key = g_key;
+        t.g_start = g_start;
+        t.list_wg = list_wg;
+        t.chunk_gid = chunk_gid;
+        t.chunk_idx = chunk_idx;
+        t.heavy_bits = heavy_bits;
+        t.max_draws = n_out;
+        t.max_wg = max_wg;
+        t.max_chunks = max_chunks;
+        t.cap_wg = pl.cap_wg;
+        t.cap_chunks = pl.cap_chunks;
+        rc = sample_step_tp(g, draw, a, sp, t, stream);
         if (rc != ND_OK) return rc;
     }
+    mark_phase(ND_PHASE_NONE, stream);
     return ND_OK;
 }
 

@@ -22,6 +22,12 @@ void set_error(const char* fmt, ...);
         }                                                                               \
     } while (0)
 
+// ---------------------------------------------------------------- phase timing (measurement only)
+// When enabled on the calling thread, every call of mark_phase records a HIP
+// event on the stream; the time between two marks is charged to the phase of
+// the first.  ND_PHASE_NONE closes the current interval.
+void mark_phase(int phase, hipStream_t stream);
+
 // ---------------------------------------------------------------- graph
 struct Graph {
     int64_t V = 0, E = 0;
@@ -89,8 +95,11 @@ struct StepCtl {
     uint32_t n_chunks;      // grid chunks
     uint32_t n_sub;         // transits in the sub-wavefront class
     uint32_t n_staged;      // workgroup/grid work items that staged their list in LDS
-    uint32_t pad;
+    uint32_t wg_cursor;     // next workgroup-class item to hand out
+    uint32_t grid_cursor;   // next grid chunk to hand out
+    uint32_t pad[7];
 };
+static_assert(sizeof(StepCtl) == 64, "one control block per 64 bytes");
 
 struct WsHeader {
     uint32_t status;        // bit 0: a root was out of range
@@ -144,8 +153,10 @@ __host__ __device__ inline int class_of(uint32_t draws, const SchedParams& sp) {
     if (draws <= (uint32_t)sp.wg_max) return ND_CLASS_WORKGROUP;
     return ND_CLASS_GRID;
 }
-int classify_groups(const int32_t* g_start, int64_t max_groups, StepCtl* ctl, const SchedParams& sp,
-                    int32_t* list_wg, int32_t* chunk_gid, int32_t* chunk_idx, int64_t max_chunks,
-                    hipStream_t stream);
+// Fills the workgroup list and the grid chunk list and marks their transits in heavy_bits
+// (one bit per vertex; may be null when a class is forced).
+int classify_groups(const int32_t* g_key, const int32_t* g_start, int64_t max_groups, StepCtl* ctl,
+                    const SchedParams& sp, int32_t* list_wg, int32_t* chunk_gid, int32_t* chunk_idx,
+                    int64_t max_chunks, uint32_t* heavy_bits, hipStream_t stream);
 
 }  // namespace nd

@@ -25,11 +25,27 @@ struct DrawArgs {
     int32_t* out;                 // this step's output array
 };
 
-int sample_step_tp(const Graph& gr, int draw, const DrawArgs& a, const SchedParams& sp, StepCtl* ctl,
-                   const int32_t* g_key, const int32_t* g_start, const int32_t* vals,
-                   const int32_t* list_wg, const int32_t* chunk_gid, const int32_t* chunk_idx,
-                   int64_t max_groups, int64_t max_wg, int64_t max_chunks, int64_t cap_wg,
-                   int64_t cap_chunks, int num_cus, hipStream_t stream);
+// Device arrays and launch bounds of one transit-parallel step.
+struct TpStep {
+    StepCtl* ctl;
+    const int32_t* keys;       // pairs sorted by transit: transit ...
+    const int32_t* vals;       // ... and slot in the previous step's array
+    const int32_t* g_key;      // distinct transits
+    const int32_t* g_start;    // first pair of each transit's group (+ sentinel)
+    const int32_t* list_wg;    // workgroup-class transits
+    const int32_t* chunk_gid;  // grid-class chunks: transit ...
+    const int32_t* chunk_idx;  // ... and chunk number
+    uint32_t* heavy_bits;      // one bit per vertex: set for workgroup / grid class transits
+    int64_t max_draws;         // host-known upper bounds that size the launches
+    int64_t max_wg, max_chunks;
+    int64_t cap_wg, cap_chunks;
+};
+
+int sample_step_tp(const Graph& gr, int draw, const DrawArgs& a, const SchedParams& sp,
+                   const TpStep& t, hipStream_t stream);
+
+int fill_dead_children(const Graph& gr, const int32_t* src, int64_t n_slots, int32_t m, int32_t* out,
+                       hipStream_t stream);
 
 int sample_step_sp(const Graph& gr, int draw, const DrawArgs& a, const int32_t* src, int64_t n_slots,
                    int check_roots, uint32_t* status, hipStream_t stream);

@@ -148,6 +148,21 @@ __device__ __forceinline__ int32_t draw_for_slot(const GraphView<OffT>& g, const
     return draw_node2vec(g, a, v, deg, sid, s, adj, wq);
 }
 
+// ---------------------------------------------------------------- children of dead slots
+// Output compaction keeps slots without a transit out of the pair list, so
+// nobody draws for them: their m children are set to NULL here, one lane per
+// output slot (contiguous stores).  Used when m > 2; for m <= 2 the first sort
+// pass writes them itself.
+__global__ __launch_bounds__(256) void fill_dead_kernel(const int32_t* __restrict__ src,
+                                                        int64_t n_out, FastDiv div_m, int32_t V,
+                                                        int32_t* __restrict__ out) {
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t o = (int64_t)blockIdx.x * 256 + threadIdx.x; o < n_out; o += stride) {
+        const int32_t v = src[fastdiv((uint32_t)o, div_m)];
+        if (v < 0 || v >= V) out[o] = ND_NULL_VERTEX;
+    }
+}
+
 // ---------------------------------------------------------------- sample-parallel (Section 5.1)
 template <int DRAW, typename OffT>
 __global__ __launch_bounds__(256) void sample_sp_kernel(GraphView<OffT> g, DrawArgs a,
@@ -176,85 +191,48 @@ __global__ __launch_bounds__(256) void sample_sp_kernel(GraphView<OffT> g, DrawA
 }
 
 // ---------------------------------------------------------------- sub-wavefront class
-
+// One lane per draw over the pairs sorted by transit: draw d belongs to pair
+// d / m, so the m draws of a (transit, sample) pair sit on m consecutive lanes
+// (one contiguous store per sample) and consecutive pairs share or neighbour
+// each other's transit (row offsets and adjacency lines are fetched once per
+// wavefront instruction and reused from cache).  Transits that classify_groups
+// handed to the workgroup or grid class are marked in a bitmap and skipped.
 template <int DRAW, typename OffT>
 __global__ __launch_bounds__(256) void sample_sub_kernel(GraphView<OffT> g, DrawArgs a,
-                                                         SchedParams sp,
                                                          const StepCtl* __restrict__ ctl,
-                                                         const int32_t* __restrict__ g_key,
-                                                         const int32_t* __restrict__ g_start,
-                                                         const int32_t* __restrict__ vals) {
-    __shared__ uint32_t s_off[4][65];
-    __shared__ uint32_t s_start[4][64];
-    __shared__ uint32_t s_deg[4][64];
-    __shared__ int32_t s_key[4][64];
-    __shared__ uint64_t s_rs[4][64];
-    const int lane = lane_id(), wave = wave_id();
-    const uint32_t U = ctl->U;
-    const uint32_t n_chunks = (U + 63u) >> 6;
-    const uint32_t wave_gid = blockIdx.x * 4u + (uint32_t)wave;
-    const uint32_t n_waves = gridDim.x * 4u;
-    for (uint32_t c = wave_gid; c < n_chunks; c += n_waves) {
-        // phase 1: one lane per transit
-        const uint32_t gi = c * 64u + (uint32_t)lane;
-        uint32_t draws = 0, start = 0, deg = 0;
-        uint64_t rs = 0;
-        int32_t v = ND_NULL_VERTEX;
-        if (gi < U) {
-            start = (uint32_t)g_start[gi];
-            const uint32_t size = (uint32_t)g_start[gi + 1] - start;
-            if (class_of(size * a.m, sp) == ND_CLASS_SUBWAVE) {
-                draws = size * a.m;
-                v = g_key[gi];
-                rs = (uint64_t)g.off[v];
-                deg = (uint32_t)((uint64_t)g.off[v + 1] - rs);
-            }
-        }
-        const uint32_t incl = wave_inclusive_scan(draws, lane);
-        const uint32_t total = __shfl(incl, 63, 64);
-        if (total == 0) continue;
-        s_off[wave][lane] = incl - draws;
-        if (lane == 63) s_off[wave][64] = total;
-        s_start[wave][lane] = start;
-        s_deg[wave][lane] = deg;
-        s_key[wave][lane] = v;
-        s_rs[wave][lane] = rs;
-        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-        // phase 2: one lane per draw
-        for (uint32_t d = (uint32_t)lane; d < total; d += 64u) {
-            // owner = last transit whose first draw is at or before d
-            uint32_t lo = 0, hi = 64;
-#pragma unroll
-            for (int it = 0; it < 6; ++it) {
-                const uint32_t mid = (lo + hi) >> 1;
-                if (s_off[wave][mid] <= d) lo = mid;
-                else hi = mid;
-            }
-            const uint32_t rel = d - s_off[wave][lo];
-            const uint32_t pi = fastdiv(rel, a.div_m);
-            const uint32_t jj = rel - pi * a.m;
-            const uint32_t q = (uint32_t)vals[s_start[wave][lo] + pi];
-            const uint32_t dg = s_deg[wave][lo];
-            int32_t res = ND_NULL_VERTEX;
-            if (dg > 0) {
-                const uint64_t r0 = s_rs[wave][lo];
-                res = draw_for_slot<DRAW>(g, a, s_key[wave][lo], dg, q, jj, g.col + r0,
-                                          DRAW == kDrawWeighted ? g.cumq + r0 : nullptr,
-                                          (DRAW == kDrawNode2vec && a.use_weights) ? g.wq + r0 : nullptr);
-            }
-            a.out[(uint64_t)q * a.m + jj] = res;
-        }
-        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+                                                         const int32_t* __restrict__ keys,
+                                                         const int32_t* __restrict__ vals,
+                                                         const uint32_t* __restrict__ heavy_bits) {
+    const uint32_t total = ctl->P * a.m;
+    const uint32_t stride = gridDim.x * 256u;
+    for (uint32_t d = blockIdx.x * 256u + threadIdx.x; d < total; d += stride) {
+        const uint32_t pi = fastdiv(d, a.div_m);
+        const uint32_t jj = d - pi * a.m;
+        const int32_t v = keys[pi];
+        if (heavy_bits != nullptr && ((heavy_bits[(uint32_t)v >> 5] >> ((uint32_t)v & 31u)) & 1u))
+            continue;
+        const uint32_t q = (uint32_t)vals[pi];
+        const uint64_t rs = (uint64_t)g.off[v];
+        const uint32_t deg = (uint32_t)((uint64_t)g.off[v + 1] - rs);
+        int32_t res = ND_NULL_VERTEX;
+        if (deg > 0)
+            res = draw_for_slot<DRAW>(g, a, v, deg, q, jj, g.col + rs,
+                                      DRAW == kDrawWeighted ? g.cumq + rs : nullptr,
+                                      (DRAW == kDrawNode2vec && a.use_weights) ? g.wq + rs : nullptr);
+        a.out[(uint64_t)q * a.m + jj] = res;
     }
 }
 
 // ---------------------------------------------------------------- workgroup and grid classes
+constexpr int kWgThreads = 1024;
+
 template <int DRAW>
-struct StageCap {
-    static constexpr uint32_t value = DRAW == kDrawUniform ? 12288u : (DRAW == kDrawWeighted ? 4096u : 6144u);
+struct StageCap {  // adjacency entries that fit the 64 KB of LDS a workgroup stages into
+    static constexpr uint32_t value =
+        DRAW == kDrawUniform ? 16384u : (DRAW == kDrawWeighted ? 5120u : 8192u);
 };
 
-// Draws d in [d0, d1) of group gid, by one 256-lane workgroup.
+// Draws d in [d0, d1) of group gid, by one workgroup.
 template <int DRAW, typename OffT>
 __device__ __forceinline__ void workgroup_draws(const GraphView<OffT>& g, const DrawArgs& a,
                                                 StepCtl* ctl, const int32_t* __restrict__ g_key,
@@ -270,12 +248,12 @@ __device__ __forceinline__ void workgroup_draws(const GraphView<OffT>& g, const 
     const uint32_t ndraws = d1 - d0;
     bool stage = deg > 0 && deg <= cap;
     if (a.lds_policy == 1) stage = false;
-    else if (a.lds_policy == 0) stage = stage && deg <= 16u * ndraws;
+    else if (a.lds_policy == 0) stage = stage && deg >= 1024u && deg / 4u <= ndraws;
     const int32_t* adj = g.col + rs;
     const uint64_t* cum = DRAW == kDrawWeighted ? g.cumq + rs : nullptr;
     const uint32_t* wq = (DRAW == kDrawNode2vec && a.use_weights) ? g.wq + rs : nullptr;
     if (stage) {
-        for (uint32_t i = threadIdx.x; i < deg; i += 256u) {
+        for (uint32_t i = threadIdx.x; i < deg; i += kWgThreads) {
             lds_col[i] = adj[i];
             if (DRAW == kDrawWeighted) lds_cum[i] = cum[i];
             if (DRAW == kDrawNode2vec && a.use_weights) lds_wq[i] = wq[i];
@@ -286,7 +264,7 @@ __device__ __forceinline__ void workgroup_draws(const GraphView<OffT>& g, const 
         if (DRAW == kDrawWeighted) cum = lds_cum;
         if (DRAW == kDrawNode2vec && a.use_weights) wq = lds_wq;
     }
-    for (uint32_t d = d0 + threadIdx.x; d < d1; d += 256u) {
+    for (uint32_t d = d0 + threadIdx.x; d < d1; d += kWgThreads) {
         const uint32_t pi = fastdiv(d, a.div_m);
         const uint32_t jj = d - pi * a.m;
         const uint32_t q = (uint32_t)vals[start + pi];
@@ -294,25 +272,34 @@ __device__ __forceinline__ void workgroup_draws(const GraphView<OffT>& g, const 
         if (deg > 0) res = draw_for_slot<DRAW>(g, a, v, deg, q, jj, adj, cum, wq);
         a.out[(uint64_t)q * a.m + jj] = res;
     }
-    __syncthreads();  // the LDS copy is reused by the next work item
 }
 
+// Work items (one transit, or one chunk of a grid-class transit) are handed out
+// through a device-side cursor, so workgroups that draw short items take more.
 template <int DRAW, typename OffT, bool GRID>
-__global__ __launch_bounds__(256) void sample_wg_kernel(GraphView<OffT> g, DrawArgs a, SchedParams sp,
-                                                        StepCtl* __restrict__ ctl,
-                                                        const int32_t* __restrict__ g_key,
-                                                        const int32_t* __restrict__ g_start,
-                                                        const int32_t* __restrict__ vals,
-                                                        const int32_t* __restrict__ list,
-                                                        const int32_t* __restrict__ chunk_idx,
-                                                        uint32_t list_capacity) {
+__global__ __launch_bounds__(kWgThreads) void sample_wg_kernel(GraphView<OffT> g, DrawArgs a,
+                                                               SchedParams sp,
+                                                               StepCtl* __restrict__ ctl,
+                                                               const int32_t* __restrict__ g_key,
+                                                               const int32_t* __restrict__ g_start,
+                                                               const int32_t* __restrict__ vals,
+                                                               const int32_t* __restrict__ list,
+                                                               const int32_t* __restrict__ chunk_idx,
+                                                               uint32_t list_capacity,
+                                                               uint32_t* __restrict__ heavy_bits) {
     constexpr uint32_t cap = StageCap<DRAW>::value;
     __shared__ int32_t lds_col[cap];
     __shared__ uint64_t lds_cum[DRAW == kDrawWeighted ? cap : 1];
     __shared__ uint32_t lds_wq[DRAW == kDrawNode2vec ? cap : 1];
+    __shared__ uint32_t s_item;
     uint32_t n_items = GRID ? ctl->n_chunks : ctl->n_wg;
     if (n_items > list_capacity) n_items = list_capacity;  // the lists are sized so this never bites
-    for (uint32_t i = blockIdx.x; i < n_items; i += gridDim.x) {
+    uint32_t* cursor = GRID ? &ctl->grid_cursor : &ctl->wg_cursor;
+    for (;;) {
+        if (threadIdx.x == 0) s_item = atomicAdd(cursor, 1u);
+        __syncthreads();
+        const uint32_t i = s_item;
+        if (i >= n_items) break;  // uniform: every wave of the workgroup leaves here
         const uint32_t gid = (uint32_t)list[i];
         const uint32_t size = (uint32_t)(g_start[gid + 1] - g_start[gid]);
         const uint32_t draws = size * a.m;
@@ -323,32 +310,44 @@ __global__ __launch_bounds__(256) void sample_wg_kernel(GraphView<OffT> g, DrawA
         }
         workgroup_draws<DRAW, OffT>(g, a, ctl, g_key, g_start, vals, gid, d0, d1, lds_col, lds_cum,
                                     lds_wq);
+        // un-mark the transit for the next step (the sub-wavefront kernel of this step is done)
+        if (threadIdx.x == 0 && d0 == 0 && heavy_bits != nullptr) {
+            const uint32_t v = (uint32_t)g_key[gid];
+            atomicAnd(&heavy_bits[v >> 5], ~(1u << (v & 31u)));
+        }
+        __syncthreads();  // s_item and the LDS copy are rewritten by the next item
     }
 }
 
 template <int DRAW, typename OffT>
-int launch_tp(const Graph& gr, const DrawArgs& a, const SchedParams& sp, StepCtl* ctl,
-              const int32_t* g_key, const int32_t* g_start, const int32_t* vals,
-              const int32_t* list_wg, const int32_t* chunk_gid, const int32_t* chunk_idx,
-              int64_t max_groups, int64_t max_wg, int64_t max_chunks, int64_t cap_wg,
-              int64_t cap_chunks, int num_cus, hipStream_t stream) {
+int launch_tp(const Graph& gr, const DrawArgs& a, const SchedParams& sp, const TpStep& t,
+              hipStream_t stream) {
     const GraphView<OffT> g = view_of<OffT>(gr);
-    const int64_t persistent = (int64_t)num_cus * 8;
-    int64_t sub_blocks = (max_groups + 255) / 256;
-    sub_blocks = sub_blocks < 1 ? 1 : (sub_blocks > persistent ? persistent : sub_blocks);
-    int64_t wg_blocks = max_wg < 1 ? 1 : (max_wg > persistent ? persistent : max_wg);
-    int64_t grid_blocks = max_chunks < 1 ? 1 : (max_chunks > persistent ? persistent : max_chunks);
-    if (sp.force_class == ND_CLASS_AUTO || sp.force_class == ND_CLASS_GRID)
-        hipLaunchKernelGGL((sample_wg_kernel<DRAW, OffT, true>), dim3((unsigned)grid_blocks), dim3(256),
-                           0, stream, g, a, sp, ctl, g_key, g_start, vals, chunk_gid, chunk_idx,
-                           (uint32_t)cap_chunks);
-    if (sp.force_class == ND_CLASS_AUTO || sp.force_class == ND_CLASS_WORKGROUP)
-        hipLaunchKernelGGL((sample_wg_kernel<DRAW, OffT, false>), dim3((unsigned)wg_blocks), dim3(256),
-                           0, stream, g, a, sp, ctl, g_key, g_start, vals, list_wg,
-                           (const int32_t*)nullptr, (uint32_t)cap_wg);
-    if (sp.force_class == ND_CLASS_AUTO || sp.force_class == ND_CLASS_SUBWAVE)
-        hipLaunchKernelGGL((sample_sub_kernel<DRAW, OffT>), dim3((unsigned)sub_blocks), dim3(256), 0,
-                           stream, g, a, sp, ctl, g_key, g_start, vals);
+    // sub-wavefront class: grid-stride over the draws of the live pairs
+    if (sp.force_class == ND_CLASS_AUTO || sp.force_class == ND_CLASS_SUBWAVE) {
+        int64_t blocks = (t.max_draws + 255) / 256;
+        const int64_t persistent = (int64_t)gr.num_cus * 8;
+        blocks = blocks < 1 ? 1 : (blocks > persistent ? persistent : blocks);
+        mark_phase(ND_PHASE_SAMPLE_SUB, stream);
+        hipLaunchKernelGGL((sample_sub_kernel<DRAW, OffT>), dim3((unsigned)blocks), dim3(256), 0,
+                           stream, g, a, t.ctl, t.keys, t.vals,
+                           sp.force_class == ND_CLASS_AUTO ? (const uint32_t*)t.heavy_bits : nullptr);
+    }
+    const int64_t wg_persistent = (int64_t)gr.num_cus * 2;
+    if (sp.force_class == ND_CLASS_AUTO || sp.force_class == ND_CLASS_WORKGROUP) {
+        int64_t blocks = t.max_wg < 1 ? 1 : (t.max_wg > wg_persistent ? wg_persistent : t.max_wg);
+        mark_phase(ND_PHASE_SAMPLE_WG, stream);
+        hipLaunchKernelGGL((sample_wg_kernel<DRAW, OffT, false>), dim3((unsigned)blocks),
+                           dim3(kWgThreads), 0, stream, g, a, sp, t.ctl, t.g_key, t.g_start, t.vals,
+                           t.list_wg, (const int32_t*)nullptr, (uint32_t)t.cap_wg, t.heavy_bits);
+    }
+    if (sp.force_class == ND_CLASS_AUTO || sp.force_class == ND_CLASS_GRID) {
+        int64_t blocks = t.max_chunks < 1 ? 1 : (t.max_chunks > wg_persistent ? wg_persistent : t.max_chunks);
+        mark_phase(ND_PHASE_SAMPLE_GRID, stream);
+        hipLaunchKernelGGL((sample_wg_kernel<DRAW, OffT, true>), dim3((unsigned)blocks),
+                           dim3(kWgThreads), 0, stream, g, a, sp, t.ctl, t.g_key, t.g_start, t.vals,
+                           t.chunk_gid, t.chunk_idx, (uint32_t)t.cap_chunks, t.heavy_bits);
+    }
     ND_HIP_CHECK(hipGetLastError());
     return ND_OK;
 }
@@ -368,6 +367,19 @@ int launch_sp(const Graph& gr, const DrawArgs& a, const int32_t* src, int64_t n_
 
 }  // namespace
 
+int fill_dead_children(const Graph& gr, const int32_t* src, int64_t n_slots, int32_t m, int32_t* out,
+                       hipStream_t stream) {
+    const int64_t n_out = n_slots * (int64_t)m;
+    if (n_out == 0) return ND_OK;
+    int64_t blocks = (n_out + 255) / 256;
+    const int64_t cap = (int64_t)gr.num_cus * 16;
+    if (blocks > cap) blocks = cap;
+    hipLaunchKernelGGL(fill_dead_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, src, n_out,
+                       make_fastdiv((uint32_t)m), (int32_t)gr.V, out);
+    ND_HIP_CHECK(hipGetLastError());
+    return ND_OK;
+}
+
 #define ND_DISPATCH(DRAWV, CALL)                                                         \
     do {                                                                                 \
         if (gr.off64) {                                                                  \
@@ -383,14 +395,9 @@ int launch_sp(const Graph& gr, const DrawArgs& a, const int32_t* src, int64_t n_
         }                                                                                \
     } while (0)
 
-int sample_step_tp(const Graph& gr, int draw, const DrawArgs& a, const SchedParams& sp, StepCtl* ctl,
-                   const int32_t* g_key, const int32_t* g_start, const int32_t* vals,
-                   const int32_t* list_wg, const int32_t* chunk_gid, const int32_t* chunk_idx,
-                   int64_t max_groups, int64_t max_wg, int64_t max_chunks, int64_t cap_wg,
-                   int64_t cap_chunks, int num_cus, hipStream_t stream) {
-    ND_DISPATCH(draw, (launch_tp<D, OffT>(gr, a, sp, ctl, g_key, g_start, vals, list_wg, chunk_gid,
-                                          chunk_idx, max_groups, max_wg, max_chunks, cap_wg,
-                                          cap_chunks, num_cus, stream)));
+int sample_step_tp(const Graph& gr, int draw, const DrawArgs& a, const SchedParams& sp,
+                   const TpStep& t, hipStream_t stream) {
+    ND_DISPATCH(draw, (launch_tp<D, OffT>(gr, a, sp, t, stream)));
 }
 
 int sample_step_sp(const Graph& gr, int draw, const DrawArgs& a, const int32_t* src, int64_t n_slots,

@@ -77,6 +77,8 @@ __global__ __launch_bounds__(1024) void seg_scan_kernel(uint32_t* __restrict__ t
         ctl->n_chunks = 0;
         ctl->n_sub = 0;
         ctl->n_staged = 0;
+        ctl->wg_cursor = 0;
+        ctl->grid_cursor = 0;
         g_start[carry] = (int32_t)ctl->P;  // sentinel: end of the last group
     }
 }
@@ -118,54 +120,91 @@ __global__ __launch_bounds__(kSegThreads) void seg_write_kernel(const int32_t* _
 }
 
 
-// One lane per transit.  Lanes of a wave reserve list space with one atomic per
-// class (wave-aggregated with ballots), so list order follows transit order
-// within a wave.
-__global__ __launch_bounds__(256) void classify_kernel(const int32_t* __restrict__ g_start,
+// One lane per transit, 1024 transits per workgroup round.  List space is
+// reserved with one atomic per class per round (counts are combined with wave64
+// ballots and a small LDS table first), so list order follows transit order
+// inside a round.  Workgroup- and grid-class transits are marked in heavy_bits
+// so that the sub-wavefront kernel leaves their pairs alone.
+__global__ __launch_bounds__(256) void classify_kernel(const int32_t* __restrict__ g_key,
+                                                       const int32_t* __restrict__ g_start,
                                                        StepCtl* __restrict__ ctl, SchedParams sp,
                                                        int32_t* __restrict__ list_wg,
                                                        int32_t* __restrict__ chunk_gid,
                                                        int32_t* __restrict__ chunk_idx,
-                                                       int64_t max_chunks) {
-    const int lane = lane_id();
+                                                       int64_t max_chunks,
+                                                       uint32_t* __restrict__ heavy_bits) {
+    constexpr int R = 4;
+    __shared__ uint32_t s_wg[R * 4 + 1], s_ch[R * 4 + 1], s_stat[2];
+    const int lane = lane_id(), wave = wave_id();
     const int64_t U = ctl->U;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t base = (int64_t)blockIdx.x * blockDim.x; base < U; base += stride) {
-        const int64_t g = base + threadIdx.x;
-        int cls = -1;
-        uint32_t draws = 0;
-        if (g < U) {
-            draws = (uint32_t)(g_start[g + 1] - g_start[g]) * (uint32_t)sp.m;
-            cls = class_of(draws, sp);
-        }
-        const uint64_t b_sub = __ballot(cls == ND_CLASS_SUBWAVE);
-        const uint64_t b_wg = __ballot(cls == ND_CLASS_WORKGROUP);
-        const uint64_t b_grid = __ballot(cls == ND_CLASS_GRID);
-        uint32_t wg_base = 0;
-        if (lane == 0) {
-            if (b_sub) atomicAdd(&ctl->n_sub, (uint32_t)__popcll(b_sub));
-            if (b_wg) wg_base = atomicAdd(&ctl->n_wg, (uint32_t)__popcll(b_wg));
-            if (b_grid) atomicAdd(&ctl->n_grid, (uint32_t)__popcll(b_grid));
-        }
-        wg_base = __shfl(wg_base, 0, 64);
-        if (cls == ND_CLASS_WORKGROUP)
-            list_wg[wg_base + (uint32_t)__popcll(b_wg & lanes_below(lane))] = (int32_t)g;
-        if (b_grid) {  // uniform for the wave
-            const uint32_t chunks = cls == ND_CLASS_GRID
-                                        ? (draws + (uint32_t)sp.wg_max - 1u) / (uint32_t)sp.wg_max
+    const int64_t stride = (int64_t)gridDim.x * 256 * R;
+    for (int64_t base = (int64_t)blockIdx.x * 256 * R; base < U; base += stride) {
+        int cls[R];
+        uint32_t draws[R], wgrank[R], chexcl[R];
+        uint32_t n_sub = 0, n_grid = 0;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int64_t g = base + r * 256 + threadIdx.x;
+            cls[r] = -1;
+            draws[r] = 0;
+            if (g < U) {
+                draws[r] = (uint32_t)(g_start[g + 1] - g_start[g]) * (uint32_t)sp.m;
+                cls[r] = class_of(draws[r], sp);
+            }
+            const uint64_t b_wg = __ballot(cls[r] == ND_CLASS_WORKGROUP);
+            wgrank[r] = (uint32_t)__popcll(b_wg & lanes_below(lane));
+            const uint32_t chunks = cls[r] == ND_CLASS_GRID
+                                        ? (draws[r] + (uint32_t)sp.wg_max - 1u) / (uint32_t)sp.wg_max
                                         : 0u;
             const uint32_t incl = wave_inclusive_scan(chunks, lane);
-            const uint32_t total = __shfl(incl, 63, 64);
-            uint32_t cbase = 0;
-            if (lane == 0) cbase = atomicAdd(&ctl->n_chunks, total);
-            cbase = __shfl(cbase, 0, 64) + incl - chunks;
-            for (uint32_t c = 0; c < chunks; ++c) {
-                if ((int64_t)(cbase + c) < max_chunks) {  // capacity is sized so this always holds
-                    chunk_gid[cbase + c] = (int32_t)g;
-                    chunk_idx[cbase + c] = (int32_t)c;
+            chexcl[r] = incl - chunks;
+            if (lane == 63) {
+                s_wg[r * 4 + wave] = (uint32_t)__popcll(b_wg);
+                s_ch[r * 4 + wave] = incl;
+            }
+            n_sub += (uint32_t)__popcll(__ballot(cls[r] == ND_CLASS_SUBWAVE));
+            n_grid += (uint32_t)__popcll(__ballot(cls[r] == ND_CLASS_GRID));
+        }
+        if (lane == 0) {
+            if (n_sub) atomicAdd(&ctl->n_sub, n_sub);
+            if (n_grid) atomicAdd(&ctl->n_grid, n_grid);
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            uint32_t run_wg = 0, run_ch = 0;
+            for (int i = 0; i < R * 4; ++i) {
+                const uint32_t a = s_wg[i], b = s_ch[i];
+                s_wg[i] = run_wg;
+                s_ch[i] = run_ch;
+                run_wg += a;
+                run_ch += b;
+            }
+            s_stat[0] = run_wg ? atomicAdd(&ctl->n_wg, run_wg) : 0u;
+            s_stat[1] = run_ch ? atomicAdd(&ctl->n_chunks, run_ch) : 0u;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int64_t g = base + r * 256 + threadIdx.x;
+            if (cls[r] == ND_CLASS_WORKGROUP) {
+                list_wg[s_stat[0] + s_wg[r * 4 + wave] + wgrank[r]] = (int32_t)g;
+            } else if (cls[r] == ND_CLASS_GRID) {
+                const uint32_t cbase = s_stat[1] + s_ch[r * 4 + wave] + chexcl[r];
+                const uint32_t chunks = (draws[r] + (uint32_t)sp.wg_max - 1u) / (uint32_t)sp.wg_max;
+                for (uint32_t c = 0; c < chunks; ++c) {
+                    if ((int64_t)(cbase + c) < max_chunks) {  // capacity is sized so this always holds
+                        chunk_gid[cbase + c] = (int32_t)g;
+                        chunk_idx[cbase + c] = (int32_t)c;
+                    }
                 }
             }
+            if (heavy_bits != nullptr &&
+                (cls[r] == ND_CLASS_WORKGROUP || cls[r] == ND_CLASS_GRID)) {
+                const uint32_t v = (uint32_t)g_key[g];
+                atomicOr(&heavy_bits[v >> 5], 1u << (v & 31u));
+            }
         }
+        __syncthreads();  // the LDS table is rewritten by the next round
     }
 }
 
@@ -185,14 +224,14 @@ int build_groups(const int32_t* sorted_keys, int64_t max_pairs, StepCtl* ctl, in
     return ND_OK;
 }
 
-int classify_groups(const int32_t* g_start, int64_t max_groups, StepCtl* ctl, const SchedParams& sp,
-                    int32_t* list_wg, int32_t* chunk_gid, int32_t* chunk_idx, int64_t max_chunks,
-                    hipStream_t stream) {
-    int64_t blocks = (max_groups + 255) / 256;
+int classify_groups(const int32_t* g_key, const int32_t* g_start, int64_t max_groups, StepCtl* ctl,
+                    const SchedParams& sp, int32_t* list_wg, int32_t* chunk_gid, int32_t* chunk_idx,
+                    int64_t max_chunks, uint32_t* heavy_bits, hipStream_t stream) {
+    int64_t blocks = (max_groups + 1023) / 1024;
     if (blocks < 1) blocks = 1;
-    if (blocks > 4096) blocks = 4096;
-    hipLaunchKernelGGL(classify_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, g_start, ctl,
-                       sp, list_wg, chunk_gid, chunk_idx, max_chunks);
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(classify_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, g_key, g_start,
+                       ctl, sp, list_wg, chunk_gid, chunk_idx, max_chunks, heavy_bits);
     ND_HIP_CHECK(hipGetLastError());
     return ND_OK;
 }

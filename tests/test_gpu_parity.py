@@ -233,7 +233,8 @@ def test_all_walks_on_one_vertex(small):
     hub = int(np.argmax(small.degrees()))
     roots = np.full(70000, hub, dtype=np.int32)
     want = oracle.khop(og, roots, [3, 2], seed=71)
-    got, stats = gpu_sample(dg, B.ND_KHOP, roots, 71, num_steps=2, fanout=[3, 2])
+    got, stats = gpu_sample(dg, B.ND_KHOP, roots, 71, num_steps=2, fanout=[3, 2], sched_sub_max=64,
+                            sched_wg_max=8192)
     assert_steps_equal(got, want, "single hub")
     assert stats[0, 1] == 1 and stats[0, 4] == 1 and stats[0, 5] == -(-70000 * 3 // 8192)
 
