@@ -199,7 +199,8 @@ int nd_sample_status(const void* workspace_dev, void* hip_stream);
  * this workspace (waits for hip_stream).  stats receives, for each of the
  * first max_steps steps, 8 int64 values: live pairs, distinct transits,
  * transits in the sub-wavefront / workgroup / grid class, grid chunks,
- * transits staged in LDS, reserved.  Evidence for Section 6.1.2's partition.
+ * work items staged in LDS, draws made by the workgroup and grid classes.  Evidence
+ * for Section 6.1.2's partition.
  */
 int nd_sample_stats(const void* workspace_dev, void* hip_stream, int32_t max_steps,
                     int64_t* stats);

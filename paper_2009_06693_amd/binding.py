@@ -284,13 +284,12 @@ class Sampler:
         self.device = torch.device(device)
         self.workspace = torch.empty(max(self.workspace_bytes, 256), dtype=torch.uint8,
                                      device=self.device)
-        total = sum(self.step_len)
+        starts, total = [], 0
+        for n in self.step_len:                      # every step starts on a 256-byte boundary
+            starts.append(total)
+            total += (n + 63) // 64 * 64
         self._flat = torch.empty(max(total, 1), dtype=torch.int32, device=self.device)
-        self.out: List[torch.Tensor] = []
-        base = 0
-        for n in self.step_len:
-            self.out.append(self._flat[base:base + n])
-            base += n
+        self.out: List[torch.Tensor] = [self._flat[b:b + n] for b, n in zip(starts, self.step_len)]
 
     def run(self, roots: torch.Tensor, seed: int, stream=None) -> List[torch.Tensor]:
         nd_sample(self.g, self.app, self.params, roots, seed, self.out, self.workspace, stream)

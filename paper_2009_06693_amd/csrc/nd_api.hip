@@ -610,11 +610,12 @@ int nd_sample_stats(const void* workspace_dev, void* hip_stream, int32_t max_ste
         if (i < n) {
             s[0] = host_ctl[i].P;
             s[1] = host_ctl[i].U;
-            s[2] = host_ctl[i].n_sub;
+            s[2] = (int64_t)host_ctl[i].U - host_ctl[i].n_wg - host_ctl[i].n_grid;
             s[3] = host_ctl[i].n_wg;
             s[4] = host_ctl[i].n_grid;
             s[5] = host_ctl[i].n_chunks;
             s[6] = host_ctl[i].n_staged;
+            s[7] = host_ctl[i].heavy_draws;
         }
     }
     return ND_OK;

@@ -76,6 +76,7 @@ __global__ __launch_bounds__(1024) void seg_scan_kernel(uint32_t* __restrict__ t
         ctl->n_grid = 0;
         ctl->n_chunks = 0;
         ctl->n_sub = 0;
+        ctl->heavy_draws = 0;
         ctl->n_staged = 0;
         ctl->wg_cursor = 0;
         ctl->grid_cursor = 0;
@@ -134,14 +135,13 @@ __global__ __launch_bounds__(256) void classify_kernel(const int32_t* __restrict
                                                        int64_t max_chunks,
                                                        uint32_t* __restrict__ heavy_bits) {
     constexpr int R = 4;
-    __shared__ uint32_t s_wg[R * 4 + 1], s_ch[R * 4 + 1], s_stat[2];
+    __shared__ uint32_t s_wg[R * 4 + 1], s_ch[R * 4 + 1], s_stat[2], s_grid[R * 4], s_heavy[R * 4];
     const int lane = lane_id(), wave = wave_id();
     const int64_t U = ctl->U;
     const int64_t stride = (int64_t)gridDim.x * 256 * R;
     for (int64_t base = (int64_t)blockIdx.x * 256 * R; base < U; base += stride) {
         int cls[R];
         uint32_t draws[R], wgrank[R], chexcl[R];
-        uint32_t n_sub = 0, n_grid = 0;
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int64_t g = base + r * 256 + threadIdx.x;
@@ -158,29 +158,32 @@ __global__ __launch_bounds__(256) void classify_kernel(const int32_t* __restrict
                                         : 0u;
             const uint32_t incl = wave_inclusive_scan(chunks, lane);
             chexcl[r] = incl - chunks;
+            const uint32_t heavy = wave_inclusive_scan(cls[r] == ND_CLASS_SUBWAVE ? 0u : draws[r], lane);
+            const uint64_t b_grid = __ballot(cls[r] == ND_CLASS_GRID);
             if (lane == 63) {
                 s_wg[r * 4 + wave] = (uint32_t)__popcll(b_wg);
                 s_ch[r * 4 + wave] = incl;
+                s_grid[r * 4 + wave] = (uint32_t)__popcll(b_grid);
+                s_heavy[r * 4 + wave] = heavy;
             }
-            n_sub += (uint32_t)__popcll(__ballot(cls[r] == ND_CLASS_SUBWAVE));
-            n_grid += (uint32_t)__popcll(__ballot(cls[r] == ND_CLASS_GRID));
-        }
-        if (lane == 0) {
-            if (n_sub) atomicAdd(&ctl->n_sub, n_sub);
-            if (n_grid) atomicAdd(&ctl->n_grid, n_grid);
         }
         __syncthreads();
         if (threadIdx.x == 0) {
-            uint32_t run_wg = 0, run_ch = 0;
+            uint32_t run_wg = 0, run_ch = 0, n_grid = 0, heavy = 0;
             for (int i = 0; i < R * 4; ++i) {
                 const uint32_t a = s_wg[i], b = s_ch[i];
                 s_wg[i] = run_wg;
                 s_ch[i] = run_ch;
                 run_wg += a;
                 run_ch += b;
+                n_grid += s_grid[i];
+                heavy += s_heavy[i];
             }
+            // a round without workgroup- or grid-class transits touches no global counter
             s_stat[0] = run_wg ? atomicAdd(&ctl->n_wg, run_wg) : 0u;
             s_stat[1] = run_ch ? atomicAdd(&ctl->n_chunks, run_ch) : 0u;
+            if (n_grid) atomicAdd(&ctl->n_grid, n_grid);
+            if (heavy) atomicAdd(&ctl->heavy_draws, heavy);
         }
         __syncthreads();
 #pragma unroll

@@ -1,0 +1,152 @@
+"""GPU parity at the full sizes of the five workloads, in the launch
+configuration bench.py times (one nd_sample call over every root,
+transit-parallel, default scheduling).  The two small workloads are compared
+with the oracle in full; for the three large ones the oracle computes windows
+of consecutive samples one by one (a sample's output depends only on its own
+id, root and the seed), and properties that hold at any size are checked on
+the whole output."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2009_06693_amd import binding as B
+from paper_2009_06693_amd import inputs
+
+from gpu_util import assert_steps_equal
+
+pytestmark = pytest.mark.gpu
+
+TP, SP = B.ND_MODE_TRANSIT_PARALLEL, B.ND_MODE_SAMPLE_PARALLEL
+
+
+def _run(dg, app, roots_np, seed, **kw):
+    p = B.nd_params_init(**kw)
+    r = torch.as_tensor(roots_np, device="cuda:0")
+    s = B.Sampler(dg, app, p, int(r.numel()))
+    print(f"[config] app={app} roots={r.numel()} params={kw}", flush=True)
+    out = s.run(r, seed)
+    torch.cuda.synchronize()
+    s.status()
+    return s, out
+
+
+def _windows(n, width, count, seed):
+    rng = np.random.default_rng(seed)
+    starts = sorted(set([0, max(0, n - width)] + [int(x) for x in rng.integers(0, max(1, n - width), count)]))
+    return [(a, min(n, a + width)) for a in starts]
+
+
+def test_config1_deepwalk_full():
+    g = inputs.config1_graph()
+    dg = B.nd_graph_create(g.row_offsets, g.col_indices)
+    og = oracle.OracleGraph(g.row_offsets, g.col_indices)
+    roots = inputs.all_vertices_roots(g)
+    want = oracle.deepwalk(og, roots, 100, seed=1)
+    for mode in (TP, SP):
+        _, out = _run(dg, B.ND_DEEPWALK, roots, 1, num_steps=100, mode=mode)
+        assert_steps_equal([o.cpu().numpy() for o in out], list(want), f"config 1 mode {mode}")
+
+
+def test_config2_node2vec_and_ppr_full():
+    g = inputs.config2_graph()
+    dg = B.nd_graph_create(g.row_offsets, g.col_indices, g.weights)
+    og = oracle.OracleGraph(g.row_offsets, g.col_indices, g.weights)
+    roots = inputs.all_vertices_roots(g)
+    want = oracle.node2vec(og, roots, 100, 2.0, 0.5, seed=2, use_weights=True)
+    for mode in (TP, SP):
+        _, out = _run(dg, B.ND_NODE2VEC, roots, 2, num_steps=100, p=2.0, q=0.5, use_weights=1, mode=mode)
+        assert_steps_equal([o.cpu().numpy() for o in out], list(want), f"config 2 node2vec mode {mode}")
+    want = oracle.ppr(og, roots, 100, 0.01, seed=2, use_weights=True)
+    for mode in (TP, SP):
+        s, out = _run(dg, B.ND_PPR, roots, 2, num_steps=100, term_prob=0.01, use_weights=1, mode=mode)
+        assert_steps_equal([o.cpu().numpy() for o in out], list(want), f"config 2 ppr mode {mode}")
+    # mean walk length under termination probability 0.01 with cap 100 is about 63
+    length = (want >= 0).sum(axis=0).mean()
+    assert 55 < length < 70
+
+
+def _check_khop_windows(g, og, out, fanout, seed, windows):
+    W = np.cumprod(fanout)
+    for a, b in windows:
+        want = oracle.khop(og, np.arange(a, b, dtype=np.int32), fanout, seed=seed, sample_id_base=a)
+        for i in range(len(fanout)):
+            got = out[i][a * int(W[i]):b * int(W[i])].cpu().numpy()
+            assert np.array_equal(got, want[i].reshape(-1)), f"k-hop step {i}, samples [{a},{b})"
+
+
+def _khop_properties(g, roots_t, out, fanout):
+    """NULL exactly where the parent is NULL or has no out-edge; everything else is a vertex."""
+    off = torch.as_tensor(g.row_offsets.astype(np.int64), device="cuda:0")
+    deg = off[1:] - off[:-1]
+    parent = roots_t.to(torch.int64)
+    for i, m in enumerate(fanout):
+        alive = (parent >= 0)
+        alive &= deg[parent.clamp(min=0)] > 0
+        o = out[i].view(-1, m)
+        assert bool(((o >= 0) == alive[:, None]).all()), f"NULL pattern wrong at step {i}"
+        assert int(o.max()) < g.V
+        parent = out[i].to(torch.int64)
+        del alive, o
+
+
+def test_config3_khop_all_roots():
+    g = inputs.config3_graph()
+    dg = B.nd_graph_create(g.row_offsets, g.col_indices)
+    og = oracle.OracleGraph(g.row_offsets, g.col_indices)
+    roots = inputs.all_vertices_roots(g)
+    s, out = _run(dg, B.ND_KHOP, roots, 3, num_steps=2, fanout=[25, 10])
+    # windows of whole 1,024-root batches and one ragged last batch (233,000 = 227 * 1,024 + 552)
+    wins = [(0, 1024), (113 * 1024, 114 * 1024), (227 * 1024, g.V)]
+    _check_khop_windows(g, og, out, [25, 10], 3, wins)
+    _khop_properties(g, torch.as_tensor(roots, device="cuda:0"), out, [25, 10])
+    # a single batch run on its own reproduces its slice of the all-at-once call
+    _, one = _run(dg, B.ND_KHOP, roots[5 * 1024:6 * 1024], 3, num_steps=2, fanout=[25, 10],
+                  sample_id_base=5 * 1024)
+    assert torch.equal(one[0], out[0][5 * 1024 * 25:6 * 1024 * 25])
+    assert torch.equal(one[1], out[1][5 * 1024 * 250:6 * 1024 * 250])
+    # and the sample-parallel ablation agrees everywhere
+    _, sp = _run(dg, B.ND_KHOP, roots, 3, num_steps=2, fanout=[25, 10], mode=SP)
+    assert torch.equal(sp[0], out[0]) and torch.equal(sp[1], out[1])
+
+
+def test_config4_layer():
+    g = inputs.config4_graph()
+    dg = B.nd_graph_create(g.row_offsets, g.col_indices)
+    og = oracle.OracleGraph(g.row_offsets, g.col_indices)
+    nb = 4096
+    roots = inputs.permutation(g.V, 4)[:nb * 64].copy()
+    s, out = _run(dg, B.ND_LAYER, roots, 4, num_steps=2, fanout=[2048, 2048], roots_per_sample=64)
+    for b in (0, 1, 777, 2048, 4095):
+        want = oracle.layer(og, roots[b * 64:(b + 1) * 64], 64, [2048, 2048], seed=4, sample_id_base=b)
+        for i in range(2):
+            got = out[i][b * 2048:(b + 1) * 2048].cpu().numpy()
+            assert np.array_equal(got, want[i].reshape(-1)), f"layer step {i} batch {b}"
+    assert int(out[0].min()) >= 0 and int(out[1].max()) < g.V
+
+
+def test_config5_khop_and_deepwalk():
+    g = inputs.config5_graph()
+    assert g.row_offsets.dtype == np.int64
+    dg = B.nd_graph_create(g.row_offsets, g.col_indices)
+    og = oracle.OracleGraph(g.row_offsets, g.col_indices)
+    roots = inputs.all_vertices_roots(g)
+    roots_t = torch.as_tensor(roots, device="cuda:0")
+    s, out = _run(dg, B.ND_KHOP, roots, 5, num_steps=2, fanout=[25, 10])
+    _check_khop_windows(g, og, out, [25, 10], 5, _windows(g.V, 512, 6, 55))
+    _khop_properties(g, roots_t, out, [25, 10])
+    stats = s.stats()
+    assert stats[0, 0] == g.V and stats[1, 0] == int((out[0] >= 0).sum())
+    del s, out
+    torch.cuda.empty_cache()
+    s, out = _run(dg, B.ND_DEEPWALK, roots, 5, num_steps=100)
+    for a, b in _windows(g.V, 2048, 4, 56):
+        want = oracle.deepwalk(og, roots[a:b], 100, seed=5, sample_id_base=a)
+        for i in range(100):
+            assert np.array_equal(out[i][a:b].cpu().numpy(), want[i]), f"walk step {i} window {a}"
+    # a walk that is alive at step i was alive at step i-1
+    alive = out[0] >= 0
+    for i in range(1, 100):
+        nxt = out[i] >= 0
+        assert bool((nxt <= alive).all())
+        alive = nxt
