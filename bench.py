@@ -53,7 +53,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c5_khop", choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default="c5_khop", choices=sorted(WORKLOADS) + ["copy_calib"])
     ap.add_argument("--mode", default="tp", choices=["tp", "sp"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
@@ -71,6 +71,24 @@ def main():
     from paper_2009_06693_amd import inputs
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.workload == "copy_calib":
+        # A plain device-to-device copy of known size: the yardstick that turns the
+        # FETCH_SIZE / WRITE_SIZE counters of a profiler run into bytes.
+        n = 1 << 28                                  # 2^28 int32 = 1 GiB read + 1 GiB written
+        src = torch.arange(n, dtype=torch.int32, device="cuda:0")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            dst.copy_(src)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        print(json.dumps({"workload": "copy_calib", "bytes_read": n * 4, "bytes_written": n * 4,
+                          "ms_per_copy": round(ms, 4),
+                          "copy_GBps": round(2 * n * 4 / (ms * 1e-3) / 1e9, 1)}))
+        return
     builder, app_name, pkw, desc = WORKLOADS[args.workload]
     app = {"deepwalk": B.ND_DEEPWALK, "ppr": B.ND_PPR, "node2vec": B.ND_NODE2VEC, "khop": B.ND_KHOP,
            "layer": B.ND_LAYER}[app_name]

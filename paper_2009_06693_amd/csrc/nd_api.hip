@@ -511,19 +511,11 @@ int nd_sample(const nd_graph* h, int app, const nd_params* params, const int32_t
         SchedParams sp{m, pl.sub_max, pl.wg_max, params->sched_force_class};
         const SortPlan plan = make_sort_plan(n_slots, g.V);
         int32_t *keys = nullptr, *vals = nullptr;
-        // children of slots without a transit: the first sort pass writes them for m <= 2,
-        // a flat fill kernel (contiguous stores) otherwise
-        if (m > 2) {
-            mark_phase(ND_PHASE_FILL, stream);
-            rc = fill_dead_children(g, src, n_slots, m, step_out_dev[i], stream);
-            if (rc != ND_OK) return rc;
-        }
         mark_phase(ND_PHASE_SORT, stream);
         rc = sort_pairs(src, n_slots, (int32_t)g.V, plan, (int32_t*)(ws + pl.o_keysA),
                         (int32_t*)(ws + pl.o_valsA), (int32_t*)(ws + pl.o_keysB),
                         (int32_t*)(ws + pl.o_valsB), (uint32_t*)(ws + pl.o_hist), ctl + i,
-                        m > 2 ? nullptr : step_out_dev[i], m, i == 0 ? &hdr->status : nullptr, &keys,
-                        &vals, stream);
+                        step_out_dev[i], m, i == 0 ? &hdr->status : nullptr, &keys, &vals, stream);
         if (rc != ND_OK) return rc;
         int32_t* g_key = (int32_t*)(ws + pl.o_gkey);
         int32_t* g_start = (int32_t*)(ws + pl.o_gstart);

@@ -44,9 +44,6 @@ struct TpStep {
 int sample_step_tp(const Graph& gr, int draw, const DrawArgs& a, const SchedParams& sp,
                    const TpStep& t, hipStream_t stream);
 
-int fill_dead_children(const Graph& gr, const int32_t* src, int64_t n_slots, int32_t m, int32_t* out,
-                       hipStream_t stream);
-
 int sample_step_sp(const Graph& gr, int draw, const DrawArgs& a, const int32_t* src, int64_t n_slots,
                    int check_roots, uint32_t* status, hipStream_t stream);
 

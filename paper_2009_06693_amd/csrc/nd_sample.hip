@@ -149,44 +149,6 @@ __device__ __forceinline__ int32_t draw_for_slot(const GraphView<OffT>& g, const
     return draw_node2vec(g, a, v, deg, sid, s, adj, wq);
 }
 
-// ---------------------------------------------------------------- children of dead slots
-// Output compaction keeps slots without a transit out of the pair list, so
-// nobody draws for them: their m children are set to NULL here, one lane per
-// output slot (contiguous stores).  Used when m > 2; for m <= 2 the first sort
-// pass writes them itself.
-__global__ __launch_bounds__(256) void fill_dead_kernel(const int32_t* __restrict__ src,
-                                                        int64_t n_out, FastDiv div_m, int32_t V,
-                                                        int32_t* __restrict__ out, int aligned16) {
-    // four consecutive output slots per lane: they have at most two distinct parents
-    const int64_t n4 = aligned16 ? n_out >> 2 : 0;
-    const int64_t stride = (int64_t)gridDim.x * 256;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) {
-        const uint32_t o = (uint32_t)(i << 2);
-        const uint32_t q0 = fastdiv(o, div_m), q3 = fastdiv(o + 3u, div_m);
-        const int32_t v0 = src[q0];
-        const bool dead0 = v0 < 0 || v0 >= V;
-        bool dead3 = dead0;
-        if (q3 != q0) {
-            const int32_t v3 = src[q3];
-            dead3 = v3 < 0 || v3 >= V;
-        }
-        if (dead0 && dead3 && (div_m.d >= 3u || q3 == q0)) {
-            // (with m >= 3 the middle slots belong to q0 or q3)
-            *reinterpret_cast<int4*>(out + o) = make_int4(-1, -1, -1, -1);
-        } else if (dead0 || dead3) {
-            for (uint32_t k = 0; k < 4u; ++k) {
-                const int32_t v = src[fastdiv(o + k, div_m)];
-                if (v < 0 || v >= V) out[o + k] = ND_NULL_VERTEX;
-            }
-        }
-    }
-    // ragged tail
-    for (int64_t o = (n4 << 2) + (int64_t)blockIdx.x * 256 + threadIdx.x; o < n_out; o += stride) {
-        const int32_t v = src[fastdiv((uint32_t)o, div_m)];
-        if (v < 0 || v >= V) out[o] = ND_NULL_VERTEX;
-    }
-}
-
 // ---------------------------------------------------------------- sample-parallel (Section 5.1)
 template <int DRAW, typename OffT>
 __global__ __launch_bounds__(256) void sample_sp_kernel(GraphView<OffT> g, DrawArgs a,
@@ -391,20 +353,6 @@ int launch_sp(const Graph& gr, const DrawArgs& a, const int32_t* src, int64_t n_
 }
 
 }  // namespace
-
-int fill_dead_children(const Graph& gr, const int32_t* src, int64_t n_slots, int32_t m, int32_t* out,
-                       hipStream_t stream) {
-    const int64_t n_out = n_slots * (int64_t)m;
-    if (n_out == 0) return ND_OK;
-    int64_t blocks = (n_out / 4 + 255) / 256 + 1;
-    const int64_t cap = (int64_t)gr.num_cus * 16;
-    if (blocks > cap) blocks = cap;
-    hipLaunchKernelGGL(fill_dead_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, src, n_out,
-                       make_fastdiv((uint32_t)m), (int32_t)gr.V, out,
-                       ((uintptr_t)out & 15u) == 0 ? 1 : 0);
-    ND_HIP_CHECK(hipGetLastError());
-    return ND_OK;
-}
 
 #define ND_DISPATCH(DRAWV, CALL)                                                         \
     do {                                                                                 \

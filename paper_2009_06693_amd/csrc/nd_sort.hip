@@ -11,10 +11,11 @@
 //              in LDS, coalesced scatter                    (reads 8, writes 8 B / pair)
 // The first pass is fused with transit enumeration and output compaction: it
 // reads the previous step's output array directly (the slot index is the
-// implicit value), drops slots without a transit and writes NULL into the
-// children of those slots, so later passes and the sampling kernels only ever
-// see live pairs.
+// implicit value), drops slots without a transit and (in its upsweep) writes
+// NULL into the children of those slots, so later passes and the sampling
+// kernels only ever see live pairs.
 #include "nd_common.h"
+#include "nd_philox.h"
 #include "nd_wave.h"
 
 namespace nd {
@@ -47,15 +48,19 @@ namespace {
 constexpr int kWaves = kSortThreads / 64;
 constexpr int kPerWave = kSortTile / kWaves;  // consecutive keys owned by one wave
 
-// FIRST: keys are the raw transit array (negative = no transit), n = n_slots.
+// FIRST: keys are the raw transit array (negative = no transit), n = n_slots;
+// the pass also performs the output compaction's other half: the m children of
+// every slot without a transit receive NULL.  A wavefront's 64 consecutive
+// slots own 64*m consecutive output entries, which it fills with contiguous
+// 16-byte stores; which parent is dead comes from a ballot, not from memory.
 // otherwise: keys are live pairs, n = ctl->P.
 template <bool FIRST>
 __global__ __launch_bounds__(kSortThreads) void upsweep_kernel(
     const int32_t* __restrict__ keys, int64_t n_slots, const StepCtl* __restrict__ ctl, int shift,
     int bits, uint32_t* __restrict__ hist, int64_t num_tiles, int32_t V, int check_range,
-    uint32_t* __restrict__ status) {
+    uint32_t* __restrict__ status, int32_t* __restrict__ fill_out, FastDiv div_m, int aligned16) {
     __shared__ uint32_t h[1 << kMaxRadixBits];
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = lane_id();
     const int nbins = 1 << bits;
     const uint32_t mask = (uint32_t)nbins - 1u;
     const int64_t n = FIRST ? n_slots : (int64_t)ctl->P;
@@ -66,14 +71,45 @@ __global__ __launch_bounds__(kSortThreads) void upsweep_kernel(
     if (base < n) {
 #pragma unroll 4
         for (int i = tid; i < kSortTile; i += kSortThreads) {
-            const int64_t idx = base + i;
+            const int64_t idx = base + i;  // a wavefront covers 64 consecutive slots
+            int32_t k = ND_NULL_VERTEX;
             if (idx < n) {
-                int32_t k = keys[idx];
+                k = keys[idx];
                 if (FIRST && (k >= V || k < ND_NULL_VERTEX)) {
                     bad = true;
                     k = ND_NULL_VERTEX;
                 }
                 if (k >= 0) atomicAdd(&h[((uint32_t)k >> shift) & mask], 1u);
+            }
+            if (FIRST && fill_out != nullptr) {
+                const uint64_t dead = __ballot(idx < n && k < 0);
+                if (dead != 0) {  // uniform for the wavefront
+                    const uint32_t m = div_m.d;
+                    const int64_t slot0 = idx - lane;
+                    const int64_t out0 = slot0 * (int64_t)m;
+                    int64_t cnt = n - slot0;  // slots of this group of 64 that exist
+                    cnt = cnt > 64 ? 64 : cnt;
+                    const uint32_t n_out = (uint32_t)cnt * m;
+                    int32_t* dst = fill_out + out0;
+                    if (aligned16 && m >= 3u) {
+                        // four entries per lane: with m >= 3 they have at most two parents
+                        for (uint32_t o = (uint32_t)lane * 4u; o < n_out; o += 256u) {
+                            const uint32_t p0 = fastdiv(o, div_m);
+                            const uint32_t last = o + 3u < n_out ? o + 3u : n_out - 1u;
+                            const uint32_t p3 = fastdiv(last, div_m);
+                            const bool d0 = (dead >> p0) & 1ull, d3 = (dead >> p3) & 1ull;
+                            if (d0 && d3 && o + 3u < n_out) {
+                                *reinterpret_cast<int4*>(dst + o) = make_int4(-1, -1, -1, -1);
+                            } else if (d0 || d3) {
+                                for (uint32_t e = o; e <= last; ++e)
+                                    if ((dead >> fastdiv(e, div_m)) & 1ull) dst[e] = ND_NULL_VERTEX;
+                            }
+                        }
+                    } else {
+                        for (uint32_t o = (uint32_t)lane; o < n_out; o += 64u)
+                            if ((dead >> fastdiv(o, div_m)) & 1ull) dst[o] = ND_NULL_VERTEX;
+                    }
+                }
             }
         }
     }
@@ -107,7 +143,7 @@ __global__ __launch_bounds__(kSortThreads) void downsweep_kernel(
     const int32_t* __restrict__ keys_in, const int32_t* __restrict__ vals_in, int64_t n_slots,
     StepCtl* __restrict__ ctl, int shift, int bits, const uint32_t* __restrict__ hist,
     const uint32_t* __restrict__ bin_total, int64_t num_tiles, int32_t* __restrict__ keys_out,
-    int32_t* __restrict__ vals_out, int32_t* __restrict__ fill_out, int32_t m, int32_t V) {
+    int32_t* __restrict__ vals_out, int32_t V) {
     __shared__ uint32_t wave_hist[kWaves][1 << kMaxRadixBits];
     __shared__ uint32_t digit_start[1 << kMaxRadixBits];
     __shared__ uint32_t global_base[1 << kMaxRadixBits];
@@ -145,10 +181,6 @@ __global__ __launch_bounds__(kSortThreads) void downsweep_kernel(
             if (FIRST) {
                 if (k >= V || k < 0) k = ND_NULL_VERTEX;
                 v = (int32_t)idx;
-                if (k < 0 && fill_out != nullptr) {
-                    int32_t* dst = fill_out + idx * (int64_t)m;
-                    for (int32_t j = 0; j < m; ++j) dst[j] = ND_NULL_VERTEX;
-                }
             } else {
                 v = vals_in[idx];
             }
@@ -245,22 +277,23 @@ int sort_pairs(const int32_t* src, int64_t n_slots, int32_t V, const SortPlan& p
         if (p == 0) {
             hipLaunchKernelGGL(upsweep_kernel<true>, dim3((unsigned)tiles), dim3(kSortThreads), 0,
                                stream, kin, n_slots, ctl, shift, bits, hist, tiles, V,
-                               status_word != nullptr ? 1 : 0, status_word);
+                               status_word != nullptr ? 1 : 0, status_word, fill_out,
+                               make_fastdiv((uint32_t)m), ((uintptr_t)fill_out & 15u) == 0 ? 1 : 0);
         } else {
             hipLaunchKernelGGL(upsweep_kernel<false>, dim3((unsigned)tiles), dim3(kSortThreads), 0,
                                stream, kin, n_slots, ctl, shift, bits, hist, tiles, V, 0,
-                               (uint32_t*)nullptr);
+                               (uint32_t*)nullptr, (int32_t*)nullptr, make_fastdiv(1u), 0);
         }
         hipLaunchKernelGGL(binscan_kernel, dim3(1u << bits), dim3(256), 0, stream, hist, bin_total,
                            tiles);
         if (p == 0) {
             hipLaunchKernelGGL(downsweep_kernel<true>, dim3((unsigned)tiles), dim3(kSortThreads), 0,
                                stream, kin, vin, n_slots, ctl, shift, bits, hist, bin_total, tiles,
-                               kout, vout, fill_out, m, V);
+                               kout, vout, V);
         } else {
             hipLaunchKernelGGL(downsweep_kernel<false>, dim3((unsigned)tiles), dim3(kSortThreads), 0,
                                stream, kin, vin, n_slots, ctl, shift, bits, hist, bin_total, tiles,
-                               kout, vout, (int32_t*)nullptr, m, V);
+                               kout, vout, V);
         }
         kin = kout;
         vin = vout;
