@@ -29,6 +29,13 @@ ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 # (4 slots each) and 40 XORs; the index is one more multiply-high; 6 slots of addressing.
 ALU_SLOTS_PER_UNIFORM_DRAW = 20 * 4 + 40 + 4 + 6
 
+# HBM bytes per launch of the dominant kernel from two rocprofv3 --pmc runs (FETCH_SIZE, then
+# WRITE_SIZE; scaled by the factors a 1 GiB copy kernel gives: x2.0 and x1.0), averaged over the
+# launches of one call.  Source: profiles/c5_khop_tp_rocprofv3.md.  None where not profiled.
+MEASURED_TRAFFIC_BYTES = {
+    ("c5_khop", "tp", "sample_sub"): int((466.1 + 2511.3 + 400.0 + 2681.2) / 2 * 1048576),
+}
+
 WORKLOADS = {
     # name: (graph builder, app, params, description)
     "c5_khop": ("config5_graph", "khop", dict(num_steps=2, fanout=[25, 10]),
@@ -157,7 +164,7 @@ def main():
                    "sample_grid": "sample_wg_kernel<.., true>"}[dom],
         "bound": "alu", "achieved": round(alu_tops, 3), "peak": round(ALU_PEAK_TOPS, 3),
         "unit": "Tslot/s", "frac": round(alu_tops / ALU_PEAK_TOPS, 4),
-        "traffic": None,
+        "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, args.mode, dom)),
         "avg_launch_ms": round(avg_launch_ms, 4), "launches_per_step": launches[dom],
         "draws_per_launch": int(draws_per_launch),
         "hbm_view": {"achieved": round(hbm_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -188,9 +188,11 @@ __global__ __launch_bounds__(256) void sample_sub_kernel(GraphView<OffT> g, Draw
                                                          const StepCtl* __restrict__ ctl,
                                                          const int32_t* __restrict__ keys,
                                                          const int32_t* __restrict__ vals,
-                                                         const uint32_t* __restrict__ heavy_bits) {
+                                                         const uint32_t* heavy_bits) {
     const uint32_t total = ctl->P * a.m;
     const uint32_t stride = gridDim.x * 256u;
+    // no transit went to the other classes this step: nothing to look up in the bitmap
+    if ((ctl->n_wg | ctl->n_chunks) == 0u) heavy_bits = nullptr;
     for (uint32_t d = blockIdx.x * 256u + threadIdx.x; d < total; d += stride) {
         const uint32_t pi = fastdiv(d, a.div_m);
         const uint32_t jj = d - pi * a.m;
