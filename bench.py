@@ -22,12 +22,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# Integer issue rate of the chip: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz.  A full-rate
-# 32-bit integer instruction occupies one lane-slot, a 32x32->64 multiply four.
-ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
-# Algorithmic lane-slots of one uniform draw: Philox4x32-10 is 20 widening multiplies
-# (4 slots each) and 40 XORs; the index is one more multiply-high; 6 slots of addressing.
-ALU_SLOTS_PER_UNIFORM_DRAW = 20 * 4 + 40 + 4 + 6
+# Arithmetic view of a draw, for context: one Philox4x32-10 call is 20 widening 32x32->64
+# multiplies and 40 XORs.  A generator-only kernel (Philox + index, no memory) reaches about
+# 8e11 draws/s on this chip, so the generator alone caps a draw-per-lane kernel there.
+PHILOX_ONLY_DRAWS_PER_S = 8.0e11
 
 # HBM bytes per launch of the dominant kernel from two rocprofv3 --pmc runs (FETCH_SIZE, then
 # WRITE_SIZE; scaled by the factors a 1 GiB copy kernel gives: x2.0 and x1.0), averaged over the
@@ -146,30 +144,36 @@ def main():
     dom = max(kernel_phases, key=lambda k: phase_ms[k])
     avg_launch_ms = phase_ms[dom] / launches[dom]
     if stats is not None and dom == "sample_sub":
-        # draws of the sub-wavefront class per launch: all live pairs x m minus what the heavy
-        # classes took is not tracked per draw, so count every live pair (upper bound on work
-        # skipped is the heavy classes' share, reported separately below)
+        # draws made by the sub-wavefront kernel: those of all live pairs minus the share of the
+        # workgroup and grid classes (column 7 of the scheduling statistics)
         m_per_step = [pkw.get("fanout", [1] * len(s.step_len))[i] if app == B.ND_KHOP else 1
                       for i in range(len(s.step_len))]
-        draws = sum(int(stats[i, 0]) * m_per_step[i] for i in range(len(s.step_len)))
+        draws = sum(int(stats[i, 0]) * m_per_step[i] - int(stats[i, 7]) for i in range(len(s.step_len)))
     else:
         draws = live if dom != "sample_sp" else slots
     draws_per_launch = draws / launches[dom]
-    hbm_bytes_per_draw = 8.0 if app != B.ND_KHOP else (4.0 + 4.0 + 8.0 / 10.0)
+    # Algorithmic bytes the sampling kernel must move: per draw 4 (one adjacency entry) + 4
+    # (one output entry); per pair 8 (sorted transit and slot) + two row offsets, shared by
+    # the pair's m draws.
+    m_avg = draws / max(1, sum(int(stats[i, 0]) for i in range(len(s.step_len)))) if stats is not None else 1.0
+    off_bytes = 16.0 if g.row_offsets.dtype.itemsize == 8 else 8.0
+    hbm_bytes_per_draw = 8.0 + (8.0 + off_bytes) / max(m_avg, 1.0)
     hbm_gbs = draws_per_launch * hbm_bytes_per_draw / (avg_launch_ms * 1e-3) / 1e9
-    alu_tops = draws_per_launch * ALU_SLOTS_PER_UNIFORM_DRAW / (avg_launch_ms * 1e-3) / 1e12
+    draws_per_s = draws_per_launch / (avg_launch_ms * 1e-3)
     roofline = {
         "kernel": {"sample_sub": "sample_sub_kernel", "sample_sp": "sample_sp_kernel",
                    "layer": "layer_kernel", "sample_wg": "sample_wg_kernel<.., false>",
                    "sample_grid": "sample_wg_kernel<.., true>"}[dom],
-        "bound": "alu", "achieved": round(alu_tops, 3), "peak": round(ALU_PEAK_TOPS, 3),
-        "unit": "Tslot/s", "frac": round(alu_tops / ALU_PEAK_TOPS, 4),
+        "bound": "hbm", "achieved": round(hbm_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": round(hbm_gbs / HBM_PEAK_GBS, 4),
         "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, args.mode, dom)),
+        "algorithmic_bytes_per_launch": int(draws_per_launch * hbm_bytes_per_draw),
+        "algorithmic_bytes_per_draw": round(hbm_bytes_per_draw, 2),
         "avg_launch_ms": round(avg_launch_ms, 4), "launches_per_step": launches[dom],
         "draws_per_launch": int(draws_per_launch),
-        "hbm_view": {"achieved": round(hbm_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(hbm_gbs / HBM_PEAK_GBS, 4),
-                     "algorithmic_bytes_per_draw": hbm_bytes_per_draw},
+        "alu_view": {"draws_per_s": round(draws_per_s, 1),
+                     "generator_only_draws_per_s": PHILOX_ONLY_DRAWS_PER_S,
+                     "frac": round(draws_per_s / PHILOX_ONLY_DRAWS_PER_S, 4)},
     }
 
     cpu_baseline = None

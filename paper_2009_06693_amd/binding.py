@@ -14,7 +14,7 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libnd.so")
+LIB_PATH = os.environ.get("ND_LIB", os.path.join(_HERE, "libnd.so"))
 
 ND_MAX_FANOUT_STEPS = 8
 ND_MAX_WALK_STEPS = 4096

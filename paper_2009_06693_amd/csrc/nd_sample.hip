@@ -20,7 +20,6 @@
 //
 // What a lane draws is the same in all four: one Philox call per
 // (sample, slot, step, attempt), so the four produce identical outputs.
-#include <cstdlib>
 #include "nd_common.h"
 #include "nd_philox.h"
 #include "nd_wave.h"
@@ -183,32 +182,122 @@ __global__ __launch_bounds__(256) void sample_sp_kernel(GraphView<OffT> g, DrawA
 // each other's transit (row offsets and adjacency lines are fetched once per
 // wavefront instruction and reused from cache).  Transits that classify_groups
 // handed to the workgroup or grid class are marked in a bitmap and skipped.
+// What a lane needs to know about its pair before it can draw.
+struct PairCtx {
+    uint64_t rs;    // first adjacency entry of the transit
+    uint32_t deg;   // 0: nothing to draw (dead end)
+    uint32_t q;     // slot of the pair in the previous step's array
+    int32_t v;      // transit
+    bool mine;      // the pair exists and its transit is not left to another class
+};
+
+// Branch-free on purpose: every load is issued unconditionally (from a clamped, always valid
+// index), so the loads of the U pairs a lane handles per round are in flight together.
+template <bool HEAVY, typename OffT>
+__device__ __forceinline__ PairCtx load_pair(const GraphView<OffT>& g,
+                                             const int32_t* __restrict__ keys,
+                                             const int32_t* __restrict__ vals,
+                                             const uint32_t* heavy_bits, uint32_t pi, uint32_t P) {
+    PairCtx c;
+    const uint32_t pc = pi < P ? pi : P - 1u;  // P >= 1 whenever a lane gets here
+    c.v = keys[pc];
+    c.q = (uint32_t)vals[pc];
+    uint32_t heavy = 0;
+    if (HEAVY) heavy = (heavy_bits[(uint32_t)c.v >> 5] >> ((uint32_t)c.v & 31u)) & 1u;
+    c.rs = (uint64_t)g.off[c.v];
+    c.deg = (uint32_t)((uint64_t)g.off[c.v + 1] - c.rs);
+    c.mine = pi < P && heavy == 0u;
+    return c;
+}
+
+template <int DRAW, typename OffT>
+__device__ __forceinline__ int32_t draw_pair(const GraphView<OffT>& g, const DrawArgs& a,
+                                             const PairCtx& c, uint32_t jj) {
+    if (DRAW == kDrawUniform) {
+        // straight-line: the generator runs on every lane, the gather reads entry 0 of the
+        // adjacency array for lanes that have nothing to draw
+        const uint32_t s = fastdiv(c.q, a.div_wprev);
+        const uint32_t slot = (c.q - s * a.div_wprev.d) * a.m + jj;
+        const Rand4 r = draw4(a.seed, a.sample_base + s, slot, a.step, 0u);
+        const bool live = c.mine && c.deg > 0u && !(a.ppr_thr != 0 && (uint64_t)r.r3 < a.ppr_thr);
+        const uint64_t e = live ? c.rs + mulhi32(r.r0, c.deg) : 0ull;
+        const int32_t u = g.col[e];
+        return live ? u : ND_NULL_VERTEX;
+    }
+    if (!c.mine || c.deg == 0) return ND_NULL_VERTEX;
+    return draw_for_slot<DRAW>(g, a, c.v, c.deg, c.q, jj, g.col + c.rs,
+                               DRAW == kDrawWeighted ? g.cumq + c.rs : nullptr,
+                               (DRAW == kDrawNode2vec && a.use_weights) ? g.wq + c.rs : nullptr);
+}
+
+// The loop of the sub-wavefront kernel.  HEAVY: some transits of this step belong to the
+// workgroup / grid class and must be skipped (looked up in the bitmap).
+template <int DRAW, bool HEAVY, typename OffT>
+__device__ __forceinline__ void sub_loop(const GraphView<OffT>& g, const DrawArgs& a, uint32_t P,
+                                         const int32_t* __restrict__ keys,
+                                         const int32_t* __restrict__ vals,
+                                         const uint32_t* heavy_bits, uint32_t pairs_per_block) {
+    constexpr int U = 2;  // independent pairs in flight per lane
+    if (pairs_per_block != 0u) {
+        // A workgroup round covers pairs_per_block whole pairs: a lane keeps its draw index jj
+        // and walks over pairs, so no division sits in the loop.  U pairs are fetched before the
+        // first draw so that their memory latencies overlap; they are adjacent blocks of the
+        // sorted array, so the whole grid works on one contiguous window of transits at a time
+        // (that window is what L2 keeps hot).
+        const uint32_t pl = fastdiv(threadIdx.x, a.div_m);
+        const uint32_t jj = threadIdx.x - pl * a.m;
+        if (pl >= pairs_per_block) return;
+        const uint32_t stride = gridDim.x * pairs_per_block * U;
+        uint32_t pi = blockIdx.x * pairs_per_block * U + pl;
+        if (pi >= P) return;
+        // Software pipeline: the pair data of the next round is requested before this round's
+        // draws, and this round's stores are issued last, so neither the stores' acknowledgements
+        // nor the next loads are waited for while the generator runs.
+        PairCtx cur[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            cur[u] = load_pair<HEAVY>(g, keys, vals, heavy_bits, pi + u * pairs_per_block, P);
+        for (; pi < P; pi += stride) {
+            PairCtx nxt[U];
+            int32_t res[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                nxt[u] = load_pair<HEAVY>(g, keys, vals, heavy_bits,
+                                          pi + stride + u * pairs_per_block, P);
+#pragma unroll
+            for (int u = 0; u < U; ++u) res[u] = draw_pair<DRAW>(g, a, cur[u], jj);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (cur[u].mine) a.out[cur[u].q * a.m + jj] = res[u];  // below 2^31 by the call's plan
+                cur[u] = nxt[u];
+            }
+        }
+    } else {
+        const uint32_t total = P * a.m;
+        const uint32_t stride = gridDim.x * 256u;
+        for (uint32_t d = blockIdx.x * 256u + threadIdx.x; d < total; d += stride) {
+            const uint32_t pi = fastdiv(d, a.div_m);
+            const uint32_t jj = d - pi * a.m;
+            const PairCtx c = load_pair<HEAVY>(g, keys, vals, heavy_bits, pi, P);
+            const int32_t res = draw_pair<DRAW>(g, a, c, jj);
+            if (c.mine) a.out[c.q * a.m + jj] = res;
+        }
+    }
+}
+
 template <int DRAW, typename OffT>
 __global__ __launch_bounds__(256) void sample_sub_kernel(GraphView<OffT> g, DrawArgs a,
                                                          const StepCtl* __restrict__ ctl,
                                                          const int32_t* __restrict__ keys,
                                                          const int32_t* __restrict__ vals,
-                                                         const uint32_t* heavy_bits) {
-    const uint32_t total = ctl->P * a.m;
-    const uint32_t stride = gridDim.x * 256u;
+                                                         const uint32_t* heavy_bits,
+                                                         uint32_t pairs_per_block) {
+    const uint32_t P = ctl->P;
     // no transit went to the other classes this step: nothing to look up in the bitmap
-    if ((ctl->n_wg | ctl->n_chunks) == 0u) heavy_bits = nullptr;
-    for (uint32_t d = blockIdx.x * 256u + threadIdx.x; d < total; d += stride) {
-        const uint32_t pi = fastdiv(d, a.div_m);
-        const uint32_t jj = d - pi * a.m;
-        const int32_t v = keys[pi];
-        if (heavy_bits != nullptr && ((heavy_bits[(uint32_t)v >> 5] >> ((uint32_t)v & 31u)) & 1u))
-            continue;
-        const uint32_t q = (uint32_t)vals[pi];
-        const uint64_t rs = (uint64_t)g.off[v];
-        const uint32_t deg = (uint32_t)((uint64_t)g.off[v + 1] - rs);
-        int32_t res = ND_NULL_VERTEX;
-        if (deg > 0)
-            res = draw_for_slot<DRAW>(g, a, v, deg, q, jj, g.col + rs,
-                                      DRAW == kDrawWeighted ? g.cumq + rs : nullptr,
-                                      (DRAW == kDrawNode2vec && a.use_weights) ? g.wq + rs : nullptr);
-        a.out[(uint64_t)q * a.m + jj] = res;
-    }
+    if (heavy_bits != nullptr && (ctl->n_wg | ctl->n_chunks) != 0u)
+        sub_loop<DRAW, true>(g, a, P, keys, vals, heavy_bits, pairs_per_block);
+    else
+        sub_loop<DRAW, false>(g, a, P, keys, vals, heavy_bits, pairs_per_block);
 }
 
 // ---------------------------------------------------------------- workgroup and grid classes
@@ -314,13 +403,16 @@ int launch_tp(const Graph& gr, const DrawArgs& a, const SchedParams& sp, const T
     // sub-wavefront class: grid-stride over the draws of the live pairs
     if (sp.force_class == ND_CLASS_AUTO || sp.force_class == ND_CLASS_SUBWAVE) {
         int64_t blocks = (t.max_draws + 255) / 256;
-        static const int per_cu = getenv("ND_SUB_BLOCKS_PER_CU") ? atoi(getenv("ND_SUB_BLOCKS_PER_CU")) : 8;
-        const int64_t persistent = (int64_t)gr.num_cus * per_cu;
+        const int64_t persistent = (int64_t)gr.num_cus * 8;  // 8 waves per SIMD
         blocks = blocks < 1 ? 1 : (blocks > persistent ? persistent : blocks);
         mark_phase(ND_PHASE_SAMPLE_SUB, stream);
+        // whole pairs per 256-lane round when that idles under a tenth of the lanes
+        uint32_t ppb = a.m <= 256u ? 256u / a.m : 0u;
+        if (ppb * a.m < 231u) ppb = 0u;
         hipLaunchKernelGGL((sample_sub_kernel<DRAW, OffT>), dim3((unsigned)blocks), dim3(256), 0,
                            stream, g, a, t.ctl, t.keys, t.vals,
-                           sp.force_class == ND_CLASS_AUTO ? (const uint32_t*)t.heavy_bits : nullptr);
+                           sp.force_class == ND_CLASS_AUTO ? (const uint32_t*)t.heavy_bits : nullptr,
+                           ppb);
     }
     const int64_t wg_persistent = (int64_t)gr.num_cus * 2;
     if (sp.force_class == ND_CLASS_AUTO || sp.force_class == ND_CLASS_WORKGROUP) {
