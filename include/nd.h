@@ -234,8 +234,8 @@ int nd_group_by_transit(const int32_t* transits_dev, int64_t n, int64_t V,
  * ms[ND_PHASE_COUNT] and intervals[ND_PHASE_COUNT] (the caller zeroes them),
  * and resets the recording.  At most 16384 events are kept between reads;
  * later marks are dropped and nd_profile_read then returns ND_ERR_BAD_ARGUMENT.
- * The sub-wavefront, workgroup and grid phases each contain exactly one kernel
- * launch per step.
+ * The sub-wavefront phase and the workgroup/grid phase each contain exactly one
+ * kernel launch per step.
  */
 typedef enum nd_phase {
     ND_PHASE_NONE = -1,
@@ -244,8 +244,8 @@ typedef enum nd_phase {
     ND_PHASE_SORT = 2,        /* transit enumeration + radix sort by transit        */
     ND_PHASE_GROUP = 3,       /* segmented scan + classification                    */
     ND_PHASE_SAMPLE_SUB = 4,  /* sub-wavefront class kernel                         */
-    ND_PHASE_SAMPLE_WG = 5,   /* workgroup class kernel                             */
-    ND_PHASE_SAMPLE_GRID = 6, /* grid class kernel                                  */
+    ND_PHASE_SAMPLE_WG = 5,   /* workgroup and grid class kernel (one launch)       */
+    ND_PHASE_SAMPLE_GRID = 6, /* unused                                             */
     ND_PHASE_SAMPLE_SP = 7,   /* sample-parallel kernel (ablation mode)             */
     ND_PHASE_LAYER = 8,       /* collective (layer) kernel                          */
     ND_PHASE_COUNT = 9

@@ -38,6 +38,7 @@ struct Plan {
            o_gkey = 0, o_gstart = 0, o_list_wg = 0, o_chunk_gid = 0, o_chunk_idx = 0, o_bits = 0,
            total = 0;
     int64_t bit_words = 0;
+    size_t hist_bytes = 0;     // largest histogram over the steps' sort plans
 };
 
 int64_t step_fanout(int app, const nd_params* p, int i) {
@@ -170,6 +171,8 @@ int check_params(const Graph& g, int app, const nd_params* p, int64_t num_roots,
         }
         if (ns > pl->max_slots) pl->max_slots = ns;
         if (no > pl->max_out) pl->max_out = no;
+        const size_t hb = sort_hist_bytes(make_sort_plan(ns, g.V));
+        if (hb > pl->hist_bytes) pl->hist_bytes = hb;
     }
     return ND_OK;
 }
@@ -184,8 +187,7 @@ void layout(Plan* pl, int64_t V) {
         pl->o_valsA = o; o = align_up(o + n * 4);
         pl->o_keysB = o; o = align_up(o + n * 4);
         pl->o_valsB = o; o = align_up(o + n * 4);
-        const SortPlan sp = make_sort_plan(pl->max_slots, V);
-        pl->o_hist = o; o = align_up(o + sort_hist_bytes(sp));
+        pl->o_hist = o; o = align_up(o + pl->hist_bytes);
         pl->o_tiles = o; o = align_up(o + seg_scratch_bytes(pl->max_slots));
         pl->o_gkey = o; o = align_up(o + n * 4);
         pl->o_gstart = o; o = align_up(o + (n + 1) * 4);

@@ -110,15 +110,18 @@ struct WsHeader {
 static_assert(sizeof(WsHeader) == 256, "header is one 256-byte block");
 
 // ---------------------------------------------------------------- radix sort plan
-constexpr int kSortThreads = 512;
+constexpr int kSortThreads = 512;       // large inputs: 8,192 keys per tile
 constexpr int kSortItems = 16;
-constexpr int kSortTile = kSortThreads * kSortItems;   // keys per tile
+constexpr int kSmallSortThreads = 256;  // small inputs: 2,048 keys per tile
+constexpr int kSmallSortItems = 8;
+constexpr int64_t kSmallSortLimit = 1 << 19;
 constexpr int kMaxRadixBits = 8;
 
 struct SortPlan {
     int passes;
     int bits[4];
     int shift[4];
+    int tile;               // keys per tile
     int64_t max_tiles;      // tiles of the slot array (pass 0); later passes never need more
 };
 SortPlan make_sort_plan(int64_t n_slots, int64_t V);

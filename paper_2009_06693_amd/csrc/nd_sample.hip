@@ -237,7 +237,8 @@ __device__ __forceinline__ void sub_loop(const GraphView<OffT>& g, const DrawArg
                                          const int32_t* __restrict__ keys,
                                          const int32_t* __restrict__ vals,
                                          const uint32_t* heavy_bits, uint32_t pairs_per_block) {
-    constexpr int U = 2;  // independent pairs in flight per lane
+    // independent pairs in flight per lane (the looping draws gain nothing from a second one)
+    constexpr int U = DRAW == kDrawUniform ? 2 : 1;
     if (pairs_per_block != 0u) {
         // A workgroup round covers pairs_per_block whole pairs: a lane keeps its draw index jj
         // and walks over pairs, so no division sits in the loop.  U pairs are fetched before the
@@ -351,38 +352,43 @@ __device__ __forceinline__ void workgroup_draws(const GraphView<OffT>& g, const 
     }
 }
 
-// Work items (one transit, or one chunk of a grid-class transit) are handed out
-// through a device-side cursor, so workgroups that draw short items take more.
-template <int DRAW, typename OffT, bool GRID>
+// Work items are handed out through a device-side cursor, so workgroups that draw short items
+// take more of them.  Items [0, n_wg) are the workgroup-class transits (one item draws for
+// the whole transit); items [n_wg, n_wg + n_chunks) are the chunks of the grid-class
+// transits (many workgroups share one transit).  Both classes run in this one launch.
+template <int DRAW, typename OffT>
 __global__ __launch_bounds__(kWgThreads) void sample_wg_kernel(GraphView<OffT> g, DrawArgs a,
                                                                SchedParams sp,
                                                                StepCtl* __restrict__ ctl,
                                                                const int32_t* __restrict__ g_key,
                                                                const int32_t* __restrict__ g_start,
                                                                const int32_t* __restrict__ vals,
-                                                               const int32_t* __restrict__ list,
+                                                               const int32_t* __restrict__ list_wg,
+                                                               const int32_t* __restrict__ chunk_gid,
                                                                const int32_t* __restrict__ chunk_idx,
-                                                               uint32_t list_capacity,
+                                                               uint32_t cap_wg, uint32_t cap_chunks,
                                                                uint32_t* __restrict__ heavy_bits) {
     constexpr uint32_t cap = StageCap<DRAW>::value;
     __shared__ int32_t lds_col[cap];
     __shared__ uint64_t lds_cum[DRAW == kDrawWeighted ? cap : 1];
     __shared__ uint32_t lds_wq[DRAW == kDrawNode2vec ? cap : 1];
     __shared__ uint32_t s_item;
-    uint32_t n_items = GRID ? ctl->n_chunks : ctl->n_wg;
-    if (n_items > list_capacity) n_items = list_capacity;  // the lists are sized so this never bites
-    uint32_t* cursor = GRID ? &ctl->grid_cursor : &ctl->wg_cursor;
+    uint32_t n_wg = ctl->n_wg, n_chunks = ctl->n_chunks;
+    if (n_wg > cap_wg) n_wg = cap_wg;              // the lists are sized so this never bites
+    if (n_chunks > cap_chunks) n_chunks = cap_chunks;
+    const uint32_t n_items = n_wg + n_chunks;
     for (;;) {
-        if (threadIdx.x == 0) s_item = atomicAdd(cursor, 1u);
+        if (threadIdx.x == 0) s_item = atomicAdd(&ctl->wg_cursor, 1u);
         __syncthreads();
         const uint32_t i = s_item;
         if (i >= n_items) break;  // uniform: every wave of the workgroup leaves here
-        const uint32_t gid = (uint32_t)list[i];
+        const bool grid = i >= n_wg;
+        const uint32_t gid = (uint32_t)(grid ? chunk_gid[i - n_wg] : list_wg[i]);
         const uint32_t size = (uint32_t)(g_start[gid + 1] - g_start[gid]);
         const uint32_t draws = size * a.m;
         uint32_t d0 = 0, d1 = draws;
-        if (GRID) {
-            d0 = (uint32_t)chunk_idx[i] * (uint32_t)sp.wg_max;
+        if (grid) {
+            d0 = (uint32_t)chunk_idx[i - n_wg] * (uint32_t)sp.wg_max;
             d1 = d0 + (uint32_t)sp.wg_max < draws ? d0 + (uint32_t)sp.wg_max : draws;
         }
         workgroup_draws<DRAW, OffT>(g, a, ctl, g_key, g_start, vals, gid, d0, d1, lds_col, lds_cum,
@@ -414,20 +420,14 @@ int launch_tp(const Graph& gr, const DrawArgs& a, const SchedParams& sp, const T
                            sp.force_class == ND_CLASS_AUTO ? (const uint32_t*)t.heavy_bits : nullptr,
                            ppb);
     }
-    const int64_t wg_persistent = (int64_t)gr.num_cus * 2;
-    if (sp.force_class == ND_CLASS_AUTO || sp.force_class == ND_CLASS_WORKGROUP) {
-        int64_t blocks = t.max_wg < 1 ? 1 : (t.max_wg > wg_persistent ? wg_persistent : t.max_wg);
+    if (sp.force_class != ND_CLASS_SUBWAVE) {
+        const int64_t wg_persistent = (int64_t)gr.num_cus * 2;
+        int64_t blocks = t.max_wg + t.max_chunks;
+        blocks = blocks < 1 ? 1 : (blocks > wg_persistent ? wg_persistent : blocks);
         mark_phase(ND_PHASE_SAMPLE_WG, stream);
-        hipLaunchKernelGGL((sample_wg_kernel<DRAW, OffT, false>), dim3((unsigned)blocks),
-                           dim3(kWgThreads), 0, stream, g, a, sp, t.ctl, t.g_key, t.g_start, t.vals,
-                           t.list_wg, (const int32_t*)nullptr, (uint32_t)t.cap_wg, t.heavy_bits);
-    }
-    if (sp.force_class == ND_CLASS_AUTO || sp.force_class == ND_CLASS_GRID) {
-        int64_t blocks = t.max_chunks < 1 ? 1 : (t.max_chunks > wg_persistent ? wg_persistent : t.max_chunks);
-        mark_phase(ND_PHASE_SAMPLE_GRID, stream);
-        hipLaunchKernelGGL((sample_wg_kernel<DRAW, OffT, true>), dim3((unsigned)blocks),
-                           dim3(kWgThreads), 0, stream, g, a, sp, t.ctl, t.g_key, t.g_start, t.vals,
-                           t.chunk_gid, t.chunk_idx, (uint32_t)t.cap_chunks, t.heavy_bits);
+        hipLaunchKernelGGL((sample_wg_kernel<DRAW, OffT>), dim3((unsigned)blocks), dim3(kWgThreads), 0,
+                           stream, g, a, sp, t.ctl, t.g_key, t.g_start, t.vals, t.list_wg, t.chunk_gid,
+                           t.chunk_idx, (uint32_t)t.cap_wg, (uint32_t)t.cap_chunks, t.heavy_bits);
     }
     ND_HIP_CHECK(hipGetLastError());
     return ND_OK;

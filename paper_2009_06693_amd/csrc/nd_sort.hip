@@ -31,7 +31,11 @@ SortPlan make_sort_plan(int64_t n_slots, int64_t V) {
         p.shift[i] = shift;
         shift += p.bits[i];
     }
-    p.max_tiles = (n_slots + kSortTile - 1) / kSortTile;
+    // Small inputs use small tiles: more workgroups in flight and a shorter dependent chain
+    // per tile (the sort is latency-bound there); large inputs use large tiles, whose longer
+    // per-digit runs make the scatter's stores contiguous.
+    p.tile = n_slots <= kSmallSortLimit ? kSmallSortThreads * kSmallSortItems : kSortThreads * kSortItems;
+    p.max_tiles = (n_slots + p.tile - 1) / p.tile;
     if (p.max_tiles < 1) p.max_tiles = 1;
     return p;
 }
@@ -45,8 +49,6 @@ size_t sort_hist_bytes(const SortPlan& p) {
 
 namespace {
 
-constexpr int kWaves = kSortThreads / 64;
-constexpr int kPerWave = kSortTile / kWaves;  // consecutive keys owned by one wave
 
 // FIRST: keys are the raw transit array (negative = no transit), n = n_slots;
 // the pass also performs the output compaction's other half: the m children of
@@ -54,8 +56,8 @@ constexpr int kPerWave = kSortTile / kWaves;  // consecutive keys owned by one w
 // slots own 64*m consecutive output entries, which it fills with contiguous
 // 16-byte stores; which parent is dead comes from a ballot, not from memory.
 // otherwise: keys are live pairs, n = ctl->P.
-template <bool FIRST>
-__global__ __launch_bounds__(kSortThreads) void upsweep_kernel(
+template <bool FIRST, int THREADS, int ITEMS>
+__global__ __launch_bounds__(THREADS) void upsweep_kernel(
     const int32_t* __restrict__ keys, int64_t n_slots, const StepCtl* __restrict__ ctl, int shift,
     int bits, uint32_t* __restrict__ hist, int64_t num_tiles, int32_t V, int check_range,
     uint32_t* __restrict__ status, int32_t* __restrict__ fill_out, FastDiv div_m, int aligned16) {
@@ -64,13 +66,14 @@ __global__ __launch_bounds__(kSortThreads) void upsweep_kernel(
     const int nbins = 1 << bits;
     const uint32_t mask = (uint32_t)nbins - 1u;
     const int64_t n = FIRST ? n_slots : (int64_t)ctl->P;
-    const int64_t base = (int64_t)blockIdx.x * kSortTile;
+    constexpr int kTile = THREADS * ITEMS;
+    const int64_t base = (int64_t)blockIdx.x * kTile;
     if (tid < nbins) h[tid] = 0;
     __syncthreads();
     bool bad = false;
     if (base < n) {
 #pragma unroll 4
-        for (int i = tid; i < kSortTile; i += kSortThreads) {
+        for (int i = tid; i < kTile; i += THREADS) {
             const int64_t idx = base + i;  // a wavefront covers 64 consecutive slots
             int32_t k = ND_NULL_VERTEX;
             if (idx < n) {
@@ -138,42 +141,46 @@ __global__ __launch_bounds__(256) void binscan_kernel(uint32_t* __restrict__ his
     if (threadIdx.x == 0) bin_total[blockIdx.x] = carry;
 }
 
-template <bool FIRST>
-__global__ __launch_bounds__(kSortThreads) void downsweep_kernel(
+template <bool FIRST, int THREADS, int ITEMS>
+__global__ __launch_bounds__(THREADS) void downsweep_kernel(
     const int32_t* __restrict__ keys_in, const int32_t* __restrict__ vals_in, int64_t n_slots,
     StepCtl* __restrict__ ctl, int shift, int bits, const uint32_t* __restrict__ hist,
     const uint32_t* __restrict__ bin_total, int64_t num_tiles, int32_t* __restrict__ keys_out,
     int32_t* __restrict__ vals_out, int32_t V) {
+    constexpr int kTile = THREADS * ITEMS;
+    constexpr int kWaves = THREADS / 64;
+    constexpr int kPerWave = kTile / kWaves;  // consecutive keys owned by one wave
+    static_assert(THREADS >= (1 << kMaxRadixBits), "one thread per digit value");
     __shared__ uint32_t wave_hist[kWaves][1 << kMaxRadixBits];
     __shared__ uint32_t digit_start[1 << kMaxRadixBits];
     __shared__ uint32_t global_base[1 << kMaxRadixBits];
     __shared__ uint32_t scan_tmp[kWaves + 2];
-    __shared__ int32_t skeys[kSortTile];
-    __shared__ int32_t svals[kSortTile];
+    __shared__ int32_t skeys[kTile];
+    __shared__ int32_t svals[kTile];
 
     const int tid = threadIdx.x, lane = lane_id(), wave = wave_id();
     const int nbins = 1 << bits;
     const uint32_t mask = (uint32_t)nbins - 1u;
     const int64_t n = FIRST ? n_slots : (int64_t)ctl->P;
-    const int64_t base = (int64_t)blockIdx.x * kSortTile;
+    const int64_t base = (int64_t)blockIdx.x * kTile;
 
     // Global start of every digit = exclusive scan of the digit totals; the sum
     // of the totals is the number of live pairs, which pass 0 publishes.
     {
         const uint32_t t = tid < nbins ? bin_total[tid] : 0u;
         uint32_t total;
-        const uint32_t ex = block_exclusive_scan<uint32_t, kSortThreads>(t, scan_tmp, &total);
+        const uint32_t ex = block_exclusive_scan<uint32_t, THREADS>(t, scan_tmp, &total);
         if (tid < nbins) global_base[tid] = ex + hist[(int64_t)tid * num_tiles + blockIdx.x];
         if (FIRST && blockIdx.x == 0 && tid == 0) ctl->P = total;
     }
     if (base >= n) return;  // uniform for the workgroup
-    for (int i = tid; i < kWaves * (1 << kMaxRadixBits); i += kSortThreads)
+    for (int i = tid; i < kWaves * (1 << kMaxRadixBits); i += THREADS)
         (&wave_hist[0][0])[i] = 0;
 
-    int32_t key[kSortItems], val[kSortItems];
-    uint32_t rank[kSortItems];
+    int32_t key[ITEMS], val[ITEMS];
+    uint32_t rank[ITEMS];
 #pragma unroll
-    for (int r = 0; r < kSortItems; ++r) {
+    for (int r = 0; r < ITEMS; ++r) {
         const int64_t idx = base + (int64_t)wave * kPerWave + r * 64 + lane;
         int32_t k = ND_NULL_VERTEX, v = 0;
         if (idx < n) {
@@ -194,7 +201,7 @@ __global__ __launch_bounds__(kSortThreads) void downsweep_kernel(
     // keys, the lanes holding the same digit are found with one ballot per digit
     // bit; the lowest such lane advances the wave's running count of the digit.
 #pragma unroll
-    for (int r = 0; r < kSortItems; ++r) {
+    for (int r = 0; r < ITEMS; ++r) {
         const bool live = key[r] >= 0;
         const uint32_t d = ((uint32_t)key[r] >> shift) & mask;
         uint64_t peers = __ballot(live);
@@ -231,7 +238,7 @@ __global__ __launch_bounds__(kSortThreads) void downsweep_kernel(
             }
         }
         uint32_t total;
-        const uint32_t ex = block_exclusive_scan<uint32_t, kSortThreads>(cnt, scan_tmp, &total);
+        const uint32_t ex = block_exclusive_scan<uint32_t, THREADS>(cnt, scan_tmp, &total);
         if (tid < nbins) digit_start[tid] = ex;
         if (tid == 0) scan_tmp[kWaves + 1] = total;  // live keys of the tile
     }
@@ -239,7 +246,7 @@ __global__ __launch_bounds__(kSortThreads) void downsweep_kernel(
     const uint32_t tile_live = scan_tmp[kWaves + 1];
 
 #pragma unroll
-    for (int r = 0; r < kSortItems; ++r) {
+    for (int r = 0; r < ITEMS; ++r) {
         if (key[r] >= 0) {
             const uint32_t d = ((uint32_t)key[r] >> shift) & mask;
             const uint32_t pos = digit_start[d] + wave_hist[wave][d] + rank[r];
@@ -249,7 +256,7 @@ __global__ __launch_bounds__(kSortThreads) void downsweep_kernel(
     }
     __syncthreads();
 
-    for (uint32_t i = tid; i < tile_live; i += kSortThreads) {
+    for (uint32_t i = tid; i < tile_live; i += THREADS) {
         const int32_t k = skeys[i];
         const uint32_t d = ((uint32_t)k >> shift) & mask;
         const uint32_t g = global_base[d] + (i - digit_start[d]);
@@ -258,12 +265,11 @@ __global__ __launch_bounds__(kSortThreads) void downsweep_kernel(
     }
 }
 
-}  // namespace
-
-int sort_pairs(const int32_t* src, int64_t n_slots, int32_t V, const SortPlan& plan, int32_t* keysA,
-               int32_t* valsA, int32_t* keysB, int32_t* valsB, uint32_t* hist, StepCtl* ctl,
-               int32_t* fill_out, int32_t m, uint32_t* status_word, int32_t** keys_out,
-               int32_t** vals_out, hipStream_t stream) {
+template <int THREADS, int ITEMS>
+int sort_pairs_impl(const int32_t* src, int64_t n_slots, int32_t V, const SortPlan& plan,
+                    int32_t* keysA, int32_t* valsA, int32_t* keysB, int32_t* valsB, uint32_t* hist,
+                    StepCtl* ctl, int32_t* fill_out, int32_t m, uint32_t* status_word,
+                    int32_t** keys_out, int32_t** vals_out, hipStream_t stream) {
     const int64_t tiles = plan.max_tiles;
     int maxbits = 0;
     for (int i = 0; i < plan.passes; ++i) maxbits = plan.bits[i] > maxbits ? plan.bits[i] : maxbits;
@@ -275,25 +281,25 @@ int sort_pairs(const int32_t* src, int64_t n_slots, int32_t V, const SortPlan& p
     for (int p = 0; p < plan.passes; ++p) {
         const int bits = plan.bits[p], shift = plan.shift[p];
         if (p == 0) {
-            hipLaunchKernelGGL(upsweep_kernel<true>, dim3((unsigned)tiles), dim3(kSortThreads), 0,
-                               stream, kin, n_slots, ctl, shift, bits, hist, tiles, V,
+            hipLaunchKernelGGL((upsweep_kernel<true, THREADS, ITEMS>), dim3((unsigned)tiles),
+                               dim3(THREADS), 0, stream, kin, n_slots, ctl, shift, bits, hist, tiles, V,
                                status_word != nullptr ? 1 : 0, status_word, fill_out,
                                make_fastdiv((uint32_t)m), ((uintptr_t)fill_out & 15u) == 0 ? 1 : 0);
         } else {
-            hipLaunchKernelGGL(upsweep_kernel<false>, dim3((unsigned)tiles), dim3(kSortThreads), 0,
-                               stream, kin, n_slots, ctl, shift, bits, hist, tiles, V, 0,
-                               (uint32_t*)nullptr, (int32_t*)nullptr, make_fastdiv(1u), 0);
+            hipLaunchKernelGGL((upsweep_kernel<false, THREADS, ITEMS>), dim3((unsigned)tiles),
+                               dim3(THREADS), 0, stream, kin, n_slots, ctl, shift, bits, hist, tiles, V,
+                               0, (uint32_t*)nullptr, (int32_t*)nullptr, make_fastdiv(1u), 0);
         }
         hipLaunchKernelGGL(binscan_kernel, dim3(1u << bits), dim3(256), 0, stream, hist, bin_total,
                            tiles);
         if (p == 0) {
-            hipLaunchKernelGGL(downsweep_kernel<true>, dim3((unsigned)tiles), dim3(kSortThreads), 0,
-                               stream, kin, vin, n_slots, ctl, shift, bits, hist, bin_total, tiles,
-                               kout, vout, V);
+            hipLaunchKernelGGL((downsweep_kernel<true, THREADS, ITEMS>), dim3((unsigned)tiles),
+                               dim3(THREADS), 0, stream, kin, vin, n_slots, ctl, shift, bits, hist,
+                               bin_total, tiles, kout, vout, V);
         } else {
-            hipLaunchKernelGGL(downsweep_kernel<false>, dim3((unsigned)tiles), dim3(kSortThreads), 0,
-                               stream, kin, vin, n_slots, ctl, shift, bits, hist, bin_total, tiles,
-                               kout, vout, V);
+            hipLaunchKernelGGL((downsweep_kernel<false, THREADS, ITEMS>), dim3((unsigned)tiles),
+                               dim3(THREADS), 0, stream, kin, vin, n_slots, ctl, shift, bits, hist,
+                               bin_total, tiles, kout, vout, V);
         }
         kin = kout;
         vin = vout;
@@ -309,6 +315,21 @@ int sort_pairs(const int32_t* src, int64_t n_slots, int32_t V, const SortPlan& p
     *keys_out = const_cast<int32_t*>(kin);
     *vals_out = const_cast<int32_t*>(vin);
     return ND_OK;
+}
+
+}  // namespace
+
+int sort_pairs(const int32_t* src, int64_t n_slots, int32_t V, const SortPlan& plan, int32_t* keysA,
+               int32_t* valsA, int32_t* keysB, int32_t* valsB, uint32_t* hist, StepCtl* ctl,
+               int32_t* fill_out, int32_t m, uint32_t* status_word, int32_t** keys_out,
+               int32_t** vals_out, hipStream_t stream) {
+    if (plan.tile == kSmallSortThreads * kSmallSortItems)
+        return sort_pairs_impl<kSmallSortThreads, kSmallSortItems>(
+            src, n_slots, V, plan, keysA, valsA, keysB, valsB, hist, ctl, fill_out, m, status_word,
+            keys_out, vals_out, stream);
+    return sort_pairs_impl<kSortThreads, kSortItems>(src, n_slots, V, plan, keysA, valsA, keysB, valsB,
+                                                     hist, ctl, fill_out, m, status_word, keys_out,
+                                                     vals_out, stream);
 }
 
 }  // namespace nd
