@@ -14,16 +14,23 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "nd_oracle.c")
-_LIB = os.path.join(_HERE, "libnd_oracle.so")
+# ND_ORACLE_LIB lets the mutation test point the pins at a deliberately broken build
+_LIB = os.environ.get("ND_ORACLE_LIB", os.path.join(_HERE, "libnd_oracle.so"))
 _lib = None
 
 NULL = -1
 
 
+def compile_oracle(src: str, lib: str) -> None:
+    subprocess.run(["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-shared", "-fPIC", src, "-o", lib,
+                    "-lm"], check=True)
+
+
 def build(force: bool = False) -> str:
+    if "ND_ORACLE_LIB" in os.environ:
+        return _LIB
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.run(["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-shared", "-fPIC", _SRC,
-                        "-o", _LIB, "-lm"], check=True)
+        compile_oracle(_SRC, _LIB)
     return _LIB
 
 

@@ -182,6 +182,27 @@ def test_layer_exact_index_arithmetic():
             assert out[b, j] == 1 + x // c
 
 
+def test_layer_draw_is_monotone_over_the_concatenation():
+    # Inverse transform over the concatenated lists: a larger random number can never select an
+    # earlier entry of the concatenation (lists in transit order, entries in adjacency order).
+    g = inputs.from_edges(7, [(0, 2), (0, 3), (0, 4), (1, 5), (1, 6)])
+    B_, m = 300, 16
+    out = oracle.layer(_og(g), np.tile(np.array([0, 1], dtype=np.int32), B_), 2, [m], seed=9)[0]
+    pos = {2: 0, 3: 1, 4: 2, 5: 3, 6: 4}
+    pairs = []
+    for b in range(B_):
+        for j in range(m):
+            r = oracle.draw(9, b, j, 0)
+            pairs.append(((int(r[0]) << 32) | int(r[1]), pos[int(out[b, j])]))
+    pairs.sort()
+    seq = [p for _, p in pairs]
+    assert all(a <= b for a, b in zip(seq, seq[1:]))
+    assert set(seq) == {0, 1, 2, 3, 4}
+    # mass of the first list: 3 * (1/9) against 2 * (1/4)
+    first = sum(1 for p in seq if p < 3)
+    assert abs(first / len(seq) - (1 / 3) / (1 / 3 + 1 / 2)) < 0.02
+
+
 def test_layer_all_dead_transits_give_null():
     g = _layer_graph()
     out = oracle.layer(_og(g), np.array([5, -1, 5, 5], dtype=np.int32), 2, [3, 3], seed=1)

@@ -1,0 +1,68 @@
+"""The pins must notice a plausible mistake anywhere in the oracle.
+
+Each case plants one mistake in a copy of oracle/nd_oracle.c (a dropped term, a
+wrong sign or index, a swapped operand), builds it on the CPU and runs the pin
+tests against that build in a subprocess: at least one pin has to fail.  The
+unmodified source must pass the same command.
+"""
+import os
+import subprocess
+import sys
+
+import pytest
+
+import oracle
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = os.path.join(ROOT, "oracle", "nd_oracle.c")
+PINS = ["tests/test_oracle_primitives.py", "tests/test_oracle_walks.py", "tests/test_oracle_khop_layer.py"]
+
+MUTANTS = {
+    "philox_multipliers_swapped": ("(uint64_t)0xD2511F53u * c0", "(uint64_t)0xD2511F53u * c2"),
+    "philox_key_word": ("(uint32_t)(p1 >> 32) ^ c1 ^ k0", "(uint32_t)(p1 >> 32) ^ c1 ^ k1"),
+    "philox_nine_rounds": ("round < 10", "round < 9"),
+    "uniform_index_shift": ("return (uint32_t)(((uint64_t)r * d) >> 32);", "return (uint32_t)(((uint64_t)r * d) >> 31) % d;"),
+    "weighted_boundary": ("if (g->cumq[lo + j] > x) return j;", "if (g->cumq[lo + j] >= x) return j;"),
+    "weight_rounding": ("floor((double)w[e] * 65536.0 + 0.5)", "floor((double)w[e] * 65536.0)"),
+    "walk_does_not_advance": ("            out[(int64_t)i * S + s] = next;\n            v = next;\n        }\n    }\n    return 0;\n}\n\n/* ------------------------------------------------------------------------ */\n/* Personalised",
+                              "            out[(int64_t)i * S + s] = next;\n        }\n    }\n    return 0;\n}\n\n/* ------------------------------------------------------------------------ */\n/* Personalised"),
+    "ppr_coin_inverted": ("if ((uint64_t)r[3] >= thr) {", "if ((uint64_t)r[3] < thr) {"),
+    "n2v_common_and_far_swapped": ("else if (has_edge(g, t, u)) bias = b_com;\n    else bias = b_far;",
+                                   "else if (has_edge(g, t, u)) bias = b_far;\n    else bias = b_com;"),
+    "n2v_return_case_dropped": ("else if (u == t) bias = b_ret;", "else if (0) bias = b_ret;"),
+    "n2v_envelope_not_max": ("(has_t ? b_max : NDO_ONE_Q16)", "(has_t ? b_ret : NDO_ONE_Q16)"),
+    "n2v_previous_transit_stale": ("            t = v;\n            v = next;", "            v = next;"),
+    "khop_parent_index": ("parent = prev[s * W_prev + j / m];", "parent = prev[s * W_prev + j % W_prev];"),
+    "khop_counter_slot": ("(uint32_t)j, (uint32_t)i, 0u, r);\n                    next = g->col[g->off[parent]",
+                          "(uint32_t)(j / m), (uint32_t)i, 0u, r);\n                    next = g->col[g->off[parent]"),
+    "layer_weight_not_squared": ("total += d * ((((uint64_t)1) << 48) / (d * d));", "total += d * ((((uint64_t)1) << 48) / d);"),
+    "layer_index_ignores_lists_in_front": ("(int64_t)((x - before) / c)", "(int64_t)((x / c) % d)"),
+    "layer_total_drops_first_transit": ("for (int64_t t = 0; t < n_prev; ++t) {\n                const int32_t v = transits[t];\n                if (!valid_vertex(g, v)) continue;\n                const uint64_t d = (uint64_t)degree(g, v);\n                if (d == 0) continue;\n                if (d >= (1u << 24)) return -4;",
+                                        "for (int64_t t = 1; t < n_prev; ++t) {\n                const int32_t v = transits[t];\n                if (!valid_vertex(g, v)) continue;\n                const uint64_t d = (uint64_t)degree(g, v);\n                if (d == 0) continue;\n                if (d >= (1u << 24)) return -4;"),
+}
+
+
+def _run_pins(lib):
+    env = dict(os.environ, ND_ORACLE_LIB=lib)
+    cmd = [sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider", *PINS]
+    return subprocess.run(cmd, cwd=ROOT, env=env, capture_output=True, text=True)
+
+
+def test_unmodified_oracle_passes_the_pins(tmp_path):
+    lib = str(tmp_path / "clean.so")
+    oracle.compile_oracle(SRC, lib)
+    r = _run_pins(lib)
+    assert r.returncode == 0, r.stdout[-2000:]
+
+
+@pytest.mark.parametrize("name", sorted(MUTANTS))
+def test_planted_mistake_is_caught(name, tmp_path):
+    old, new = MUTANTS[name]
+    text = open(SRC).read()
+    assert text.count(old) >= 1, f"mutation site for {name} not found"
+    src = tmp_path / "mutant.c"
+    src.write_text(text.replace(old, new, 1))
+    lib = str(tmp_path / "mutant.so")
+    oracle.compile_oracle(str(src), lib)
+    r = _run_pins(lib)
+    assert r.returncode != 0, f"no pin noticed the planted mistake '{name}'"

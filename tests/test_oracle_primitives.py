@@ -76,7 +76,7 @@ def test_mulhi64_against_exact_integers():
 def test_uniform_index_closed_form(d):
     # floor(r*d/2^32) takes value j exactly for r in [ceil(j*2^32/d), ceil((j+1)*2^32/d)).
     two32 = 2 ** 32
-    js = sorted({0, 1, d // 3, d // 2, d - 2, d - 1} & set(range(d)))
+    js = sorted(j for j in {0, 1, d // 3, d // 2, d - 2, d - 1} if 0 <= j < d)
     for j in js:
         first = -((-j * two32) // d)
         last = -((-(j + 1) * two32) // d) - 1
