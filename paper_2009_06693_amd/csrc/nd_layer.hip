@@ -10,6 +10,7 @@
 // concatenation by inverse transform (binary search over the running sums,
 // then an integer division by c(v) inside the chosen list) and reads that one
 // neighbour.  One workgroup per sample, as in the paper's sample-parallel draw.
+// A transit's degree and row start are fetched once per (sample, transit slot).
 //
 // c(v) = floor(2^48 / deg(v)^2) is the fixed-point squared entry of the
 // row-normalised adjacency matrix, so a vertex is drawn with probability
@@ -25,11 +26,28 @@ namespace {
 
 constexpr int kLayerThreads = 256;
 
+// Exact floor(num / c) for num < 2^24 * c: the quotient is estimated in double precision
+// (relative error 2^-52, so off by at most one for a quotient below 2^24) and corrected with
+// integer arithmetic.
+__device__ __forceinline__ uint64_t div_small_quotient(uint64_t num, uint64_t c) {
+    uint64_t q = (uint64_t)((double)num / (double)c);
+    int64_t r = (int64_t)(num - q * c);
+    if (r < 0) {
+        --q;
+        r += (int64_t)c;
+    }
+    if (r >= (int64_t)c) ++q;
+    return q;
+}
+
+// Dynamic LDS: per transit slot the running sum of masses, the weight c(v) and the first
+// adjacency entry of the transit (24 bytes), so a draw touches global memory once.
 template <typename OffT>
 __global__ __launch_bounds__(kLayerThreads) void layer_kernel(GraphView<OffT> g, LayerArgs a) {
-    __shared__ uint64_t s_incl[ND_MAX_LAYER_TRANSITS];
-    __shared__ uint64_t s_c[ND_MAX_LAYER_TRANSITS];
-    __shared__ int32_t s_v[ND_MAX_LAYER_TRANSITS];
+    extern __shared__ uint64_t lds[];
+    uint64_t* s_incl = lds;
+    uint64_t* s_c = lds + a.n_prev;
+    uint64_t* s_rs = lds + 2 * (size_t)a.n_prev;
     __shared__ uint64_t scan_tmp[kLayerThreads / 64 + 1];
     const uint32_t b = blockIdx.x;
     const int32_t* transits = a.transits + (uint64_t)b * a.n_prev;
@@ -38,16 +56,16 @@ __global__ __launch_bounds__(kLayerThreads) void layer_kernel(GraphView<OffT> g,
     bool bad = false;
     for (uint32_t base = 0; base < a.n_prev; base += kLayerThreads) {
         const uint32_t t = base + threadIdx.x;
-        uint64_t mass = 0, c = 0;
-        int32_t v = ND_NULL_VERTEX;
+        uint64_t mass = 0, c = 0, rs = 0;
         if (t < a.n_prev) {
-            v = transits[t];
+            int32_t v = transits[t];
             if (v >= g.V || v < ND_NULL_VERTEX) {
                 bad = true;
                 v = ND_NULL_VERTEX;
             }
             if (v >= 0) {
-                const uint64_t deg = (uint64_t)g.off[v + 1] - (uint64_t)g.off[v];
+                rs = (uint64_t)g.off[v];
+                const uint64_t deg = (uint64_t)g.off[v + 1] - rs;
                 if (deg > 0) {
                     c = (1ull << 48) / (deg * deg);
                     mass = deg * c;
@@ -59,7 +77,7 @@ __global__ __launch_bounds__(kLayerThreads) void layer_kernel(GraphView<OffT> g,
         if (t < a.n_prev) {
             s_incl[t] = carry + ex + mass;
             s_c[t] = c;
-            s_v[t] = v;
+            s_rs[t] = rs;
         }
         carry += total;
         __syncthreads();
@@ -79,8 +97,8 @@ __global__ __launch_bounds__(kLayerThreads) void layer_kernel(GraphView<OffT> g,
                 else lo = mid + 1;
             }
             const uint64_t before = lo ? s_incl[lo - 1] : 0ull;
-            const uint64_t idx = (x - before) / s_c[lo];
-            res = g.col[(uint64_t)g.off[s_v[lo]] + idx];
+            const uint64_t idx = div_small_quotient(x - before, s_c[lo]);
+            res = g.col[s_rs[lo] + idx];
         }
         a.out[(uint64_t)b * a.m + j] = res;
     }
@@ -90,12 +108,23 @@ __global__ __launch_bounds__(kLayerThreads) void layer_kernel(GraphView<OffT> g,
 
 int layer_step(const Graph& gr, const LayerArgs& a, int64_t num_samples, hipStream_t stream) {
     if (num_samples == 0) return ND_OK;
+    const size_t lds_bytes = (size_t)a.n_prev * 24;  // at most 96 KB of the 160 KB per CU
+    static bool attr_set = false;
+    if (!attr_set) {  // allow dynamic LDS above the default 64 KB limit
+        ND_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&layer_kernel<int64_t>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         ND_MAX_LAYER_TRANSITS * 24));
+        ND_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&layer_kernel<int32_t>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         ND_MAX_LAYER_TRANSITS * 24));
+        attr_set = true;
+    }
     if (gr.off64)
-        hipLaunchKernelGGL(layer_kernel<int64_t>, dim3((unsigned)num_samples), dim3(kLayerThreads), 0,
-                           stream, view_of<int64_t>(gr), a);
+        hipLaunchKernelGGL(layer_kernel<int64_t>, dim3((unsigned)num_samples), dim3(kLayerThreads),
+                           lds_bytes, stream, view_of<int64_t>(gr), a);
     else
-        hipLaunchKernelGGL(layer_kernel<int32_t>, dim3((unsigned)num_samples), dim3(kLayerThreads), 0,
-                           stream, view_of<int32_t>(gr), a);
+        hipLaunchKernelGGL(layer_kernel<int32_t>, dim3((unsigned)num_samples), dim3(kLayerThreads),
+                           lds_bytes, stream, view_of<int32_t>(gr), a);
     ND_HIP_CHECK(hipGetLastError());
     return ND_OK;
 }
