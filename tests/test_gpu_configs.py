@@ -150,3 +150,24 @@ def test_config5_khop_and_deepwalk():
         nxt = out[i] >= 0
         assert bool((nxt <= alive).all())
         alive = nxt
+
+
+def test_largest_slot_count_a_call_accepts():
+    """k-hop whose last step has 2,097,152,000 slots (the ABI's limit is 2^31 - 1 per step):
+    every 32-bit index in the kernels is exercised near its top."""
+    g = inputs.config5_graph()
+    dg = B.nd_graph_create(g.row_offsets, g.col_indices)
+    og = oracle.OracleGraph(g.row_offsets, g.col_indices)
+    roots = inputs.all_vertices_roots(g)
+    p = B.nd_params_init(num_steps=2, fanout=[25, 21])
+    with pytest.raises(B.NdError) as e:
+        B.nd_sample_query(dg, B.ND_KHOP, p, g.V)
+    assert e.value.code == B.ND_ERR_TOO_LARGE
+    s, out = _run(dg, B.ND_KHOP, roots, 6, num_steps=2, fanout=[25, 20])
+    assert out[1].numel() == g.V * 500
+    wins = [(0, 256), (g.V // 2 + 77, g.V // 2 + 333), (g.V - 256, g.V)]
+    _check_khop_windows(g, og, out, [25, 20], 6, wins)
+    # the last entries of the 8.4 GB array belong to the last root
+    last = out[1][-500:].cpu().numpy()
+    want = oracle.khop(og, roots[-1:], [25, 20], seed=6, sample_id_base=g.V - 1)[1].reshape(-1)
+    assert np.array_equal(last, want)
