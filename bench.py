@@ -64,6 +64,8 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--sub-max", type=int, default=0)
     ap.add_argument("--wg-max", type=int, default=0)
+    ap.add_argument("--force-class", type=int, default=-1,
+                    help="ablation: -1 balanced (default), 0/1/2 every transit sub-wavefront/workgroup/grid")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only; sampling shards by samples with the "
@@ -107,7 +109,8 @@ def main():
         roots_np = np.arange(g.V, dtype=np.int32)
     roots = torch.as_tensor(roots_np, device="cuda:0")
     mode = B.ND_MODE_TRANSIT_PARALLEL if args.mode == "tp" else B.ND_MODE_SAMPLE_PARALLEL
-    p = B.nd_params_init(mode=mode, sched_sub_max=args.sub_max, sched_wg_max=args.wg_max, **pkw)
+    p = B.nd_params_init(mode=mode, sched_sub_max=args.sub_max, sched_wg_max=args.wg_max,
+                         sched_force_class=args.force_class, **pkw)
     s = B.Sampler(dg, app, p, int(roots.numel()))
     seed = 1
 
