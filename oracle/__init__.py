@@ -63,6 +63,8 @@ def _load():
         L.ndo_node2vec.restype = ctypes.c_int
         L.ndo_node2vec.argtypes = [vp, ctypes.c_int, dbl, dbl, ctypes.c_int, i32, vp, i64, u64, u64,
                                    i32, vp]
+        L.ndo_multirw.restype = ctypes.c_int
+        L.ndo_multirw.argtypes = [vp, i32, vp, i64, u64, u64, i32, vp]
         L.ndo_khop.restype = ctypes.c_int
         L.ndo_khop.argtypes = [vp, vp, i32, vp, i64, u64, u64, vp]
         L.ndo_layer.restype = ctypes.c_int
@@ -156,6 +158,19 @@ def node2vec(g: OracleGraph, roots, length: int, p: float, q: float, seed: int,
     _check(_load().ndo_node2vec(g._h, int(use_weights), p, q, convention, max_attempts,
                                 r.ctypes.data, r.shape[0], sample_id_base, seed, length,
                                 out.ctypes.data), "node2vec")
+    return out
+
+
+def multirw(g: OracleGraph, roots, roots_per_sample: int, length: int, seed: int,
+            sample_id_base: int = 0) -> np.ndarray:
+    """`roots` holds S * roots_per_sample vertices; returns int32 [length, S]."""
+    r = _roots(roots)
+    if r.shape[0] % roots_per_sample:
+        raise ValueError("roots must be a whole number of samples")
+    S = r.shape[0] // roots_per_sample
+    out = np.empty((length, S), dtype=np.int32)
+    _check(_load().ndo_multirw(g._h, roots_per_sample, r.ctypes.data, S, sample_id_base, seed, length,
+                               out.ctypes.data), "multirw")
     return out
 
 

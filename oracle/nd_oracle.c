@@ -307,6 +307,43 @@ int ndo_node2vec(const ndo_graph* g, int use_weights, double p, double q, int co
 }
 
 /* ------------------------------------------------------------------------ */
+/* MultiDimensional random walk (Section 3; Section 4.2, figure "Multi       */
+/* Dimensional Random Walk"): a sample owns R root vertices.  At every step  */
+/* stepTransits picks one of them uniformly, next adds a uniform neighbour   */
+/* of the picked root to the sample, and that neighbour takes the picked     */
+/* root's place.  Both choices come from the step's single generator call:   */
+/* the root index from R2, the neighbour index from R0.  A picked root that  */
+/* is NULL or has no out-edge adds NULL and leaves the roots as they are.    */
+/* roots: S*R vertices (sample-major); out[i*S + s] as for the other walks.  */
+/* ------------------------------------------------------------------------ */
+int ndo_multirw(const ndo_graph* g, int32_t R, const int32_t* roots, int64_t S,
+                uint64_t sample_id_base, uint64_t seed, int32_t L, int32_t* out) {
+    if (R < 1) return -2;
+    int32_t* cur = (int32_t*)malloc(sizeof(int32_t) * (size_t)R);
+    if (!cur) return -5;
+    for (int64_t s = 0; s < S; ++s) {
+        for (int32_t k = 0; k < R; ++k) {
+            const int32_t v = roots[s * R + k];
+            cur[k] = valid_vertex(g, v) ? v : NDO_NULL;
+        }
+        for (int32_t i = 0; i < L; ++i) {
+            uint32_t r[4];
+            draw4(seed, (uint32_t)(sample_id_base + (uint64_t)s), 0u, (uint32_t)i, 0u, r);
+            const uint32_t pick = ndo_uniform_index(r[2], (uint32_t)R);
+            const int32_t t = cur[pick];
+            int32_t next = NDO_NULL;
+            if (t != NDO_NULL && degree(g, t) > 0) {
+                next = g->col[g->off[t] + ndo_uniform_index(r[0], (uint32_t)degree(g, t))];
+                cur[pick] = next;
+            }
+            out[(int64_t)i * S + s] = next;
+        }
+    }
+    free(cur);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------ */
 /* k-hop neighbourhood sampling (Section 3; GraphSAGE's 2-hop sampler in     */
 /* Section 4.2): at step i every vertex added at step i-1 (the root at step  */
 /* 0) is a transit and contributes fanout[i] neighbours drawn uniformly and  */

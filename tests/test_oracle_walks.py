@@ -251,3 +251,56 @@ def test_node2vec_attempt_budget_changes_draws_not_the_law():
     b = oracle.node2vec(og, roots, 6, 2.0, 0.5, seed=5, use_weights=True, max_attempts=2)
     assert (a != b).any()
     assert (a[0] == b[0]).mean() > 0.5   # walks accepted within two attempts agree
+
+
+# ----------------------------------------------------------------------------- multi-dimensional walk
+
+def test_multirw_with_one_root_is_uniform_deepwalk():
+    # one root per sample: the pick is always that root and the new vertex replaces it,
+    # which is the uniform walk, draw for draw
+    g = inputs.small_graph(8, 1500, seed=3)
+    og = _og(g)
+    roots = np.arange(g.V, dtype=np.int32)
+    assert (oracle.multirw(og, roots, 1, 15, seed=9) == oracle.deepwalk(og, roots, 15, seed=9)).all()
+
+
+def test_multirw_pick_is_uniform_and_replaces_the_picked_root():
+    # directed paths a -> a+1 starting at 0, 100, 200, 300: which path advanced says which
+    # root was picked, and a path's next vertex says the picked root had been replaced
+    n = 400
+    g = inputs.from_edges(n, [(v, v + 1) for v in range(n) if v % 100 != 99])
+    og = _og(g)
+    S, L = 20000, 30
+    roots = np.tile(np.array([0, 100, 200, 300], dtype=np.int32), S)
+    out = oracle.multirw(og, roots, 4, L, seed=44)
+    first = out[0] // 100
+    assert stats.chisquare(np.bincount(first, minlength=4)).pvalue > 1e-4
+    for s in range(200):
+        pos = [0, 100, 200, 300]
+        for i in range(L):
+            v = int(out[i, s])
+            k = v // 100
+            assert v == pos[k] + 1          # the picked root is the path's current end
+            pos[k] = v
+        r2 = int(oracle.draw(44, s, 0, 0)[2])
+        assert int(out[0, s]) // 100 == (r2 * 4) >> 32
+
+
+def test_multirw_dead_pick_adds_null_and_keeps_the_roots():
+    # root 1 has no out-edge, root 0 walks a cycle
+    g = inputs.from_edges(4, [(0, 2), (2, 3), (3, 0)])
+    out = oracle.multirw(_og(g), np.tile(np.array([0, 1], dtype=np.int32), 3000), 2, 12, seed=5)
+    nulls = (out == -1)
+    assert 0.4 < nulls.mean() < 0.6          # the dead root is picked half of the time, forever
+    for s in range(50):
+        live = [int(v) for v in out[:, s] if v >= 0]
+        assert live == [[2, 3, 0][k % 3] for k in range(len(live))]
+
+
+def test_multirw_sample_id_base():
+    g = inputs.small_graph(8, 1500, seed=3)
+    og = _og(g)
+    roots = inputs.permutation(g.V, 2)[:50 * 5]
+    full = oracle.multirw(og, roots, 5, 20, seed=6)
+    part = oracle.multirw(og, roots[10 * 5:30 * 5], 5, 20, seed=6, sample_id_base=10)
+    assert (full[:, 10:30] == part).all()
