@@ -48,6 +48,8 @@ WORKLOADS = {
                "PPR termination 0.01 cap 100, 57K power-law, weights U[1,5)"),
     "c1_deepwalk": ("config1_graph", "deepwalk", dict(num_steps=100),
                     "DeepWalk length 100, R-MAT scale 12"),
+    "c5_multirw": ("config5_graph", "multirw", dict(num_steps=100, roots_per_sample=100),
+                   "multi-dimensional walk, 100 roots per sample, length 100, 41,943 samples, R-MAT scale 22"),
     "c4_layer": ("config4_graph", "layer", dict(num_steps=2, fanout=[2048, 2048], roots_per_sample=64),
                  "layer sampling 64 roots, 2 x 2,048, 4,096 batches, 3M power-law"),
 }
@@ -98,13 +100,15 @@ def main():
         return
     builder, app_name, pkw, desc = WORKLOADS[args.workload]
     app = {"deepwalk": B.ND_DEEPWALK, "ppr": B.ND_PPR, "node2vec": B.ND_NODE2VEC, "khop": B.ND_KHOP,
-           "layer": B.ND_LAYER}[app_name]
+           "layer": B.ND_LAYER, "multirw": B.ND_MULTIRW}[app_name]
     t0 = time.time()
     g = getattr(inputs, builder)()
     sys.stderr.write(f"[bench] {g.describe()} (generated in {time.time() - t0:.1f}s)\n")
     dg = B.nd_graph_create(g.row_offsets, g.col_indices, g.weights)
     if app == B.ND_LAYER:
         roots_np = inputs.permutation(g.V, 4)[:4096 * 64].copy()
+    elif app == B.ND_MULTIRW:
+        roots_np = inputs.permutation(g.V, 7)[:(g.V // 100) * 100].copy()
     else:
         roots_np = np.arange(g.V, dtype=np.int32)
     roots = torch.as_tensor(roots_np, device="cuda:0")
@@ -193,6 +197,8 @@ def main():
                 o = list(oracle.deepwalk(og, r, pkw["num_steps"], seed, use_weights=bool(pkw.get("use_weights", 0))))
             elif app == B.ND_PPR:
                 o = list(oracle.ppr(og, r, pkw["num_steps"], pkw["term_prob"], seed, use_weights=bool(pkw.get("use_weights", 0))))
+            elif app == B.ND_MULTIRW:
+                o = list(oracle.multirw(og, r, pkw["roots_per_sample"], pkw["num_steps"], seed))
             elif app == B.ND_NODE2VEC:
                 o = list(oracle.node2vec(og, r, pkw["num_steps"], pkw["p"], pkw["q"], seed, use_weights=bool(pkw.get("use_weights", 0))))
             else:

@@ -63,8 +63,11 @@ typedef enum nd_app {
     ND_PPR = 1,      /* static walk that ends with probability term_prob per step     */
     ND_NODE2VEC = 2, /* second-order walk, rejection sampling with bias p, q          */
     ND_KHOP = 3,     /* GraphSAGE k-hop: fanout[i] uniform neighbours per transit     */
-    ND_LAYER = 4     /* collective: fanout[i] draws from the transits' combined       */
+    ND_LAYER = 4,    /* collective: fanout[i] draws from the transits' combined       */
                      /* neighbourhood, LADIES-style weights                           */
+    ND_MULTIRW = 5   /* multi-dimensional walk: a sample owns roots_per_sample roots;  */
+                     /* each step picks one uniformly, adds a uniform neighbour of it  */
+                     /* and puts that neighbour in the picked root's place             */
 } nd_app;
 
 /* Execution strategy.  Both give identical outputs. */
@@ -95,7 +98,8 @@ typedef struct nd_params {
                                /* (the wording of Section 4.2)                         */
     double p, q;               /* node2vec hyper-parameters                            */
     double term_prob;          /* PPR: probability of ending the walk at each step     */
-    int32_t roots_per_sample;  /* layer: roots that form one sample (batch)            */
+    int32_t roots_per_sample;  /* layer: roots that form one sample (batch); multi-    */
+                               /* dimensional walk: roots a sample owns (at most 4,096) */
     int32_t n2v_max_attempts;  /* node2vec: rejection attempts before the exact        */
                                /* fallback draw; part of the output's definition       */
     uint64_t sample_id_base;   /* id of this call's first sample in the random-number  */
@@ -150,8 +154,9 @@ int nd_graph_info(const nd_graph* g, int64_t* V, int64_t* E, int* has_weights,
 
 /*
  * Sizes of one nd_sample call.
- *   num_roots        walks and k-hop: one sample per root; layer: a multiple of
- *                    roots_per_sample (one sample per group of roots)
+ *   num_roots        walks and k-hop: one sample per root; layer and multi-
+ *                    dimensional walk: a multiple of roots_per_sample (one sample
+ *                    per group of consecutive roots)
  *   num_steps        out: number of per-step output arrays
  *   step_len         out, host, at least num_steps entries (ND_MAX_WALK_STEPS is
  *                    always enough): int32 elements of each step's array.

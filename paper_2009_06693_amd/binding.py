@@ -20,7 +20,7 @@ ND_MAX_FANOUT_STEPS = 8
 ND_MAX_WALK_STEPS = 4096
 ND_NULL_VERTEX = -1
 
-ND_DEEPWALK, ND_PPR, ND_NODE2VEC, ND_KHOP, ND_LAYER = range(5)
+ND_DEEPWALK, ND_PPR, ND_NODE2VEC, ND_KHOP, ND_LAYER, ND_MULTIRW = range(6)
 ND_MODE_TRANSIT_PARALLEL, ND_MODE_SAMPLE_PARALLEL = 0, 1
 ND_CLASS_AUTO, ND_CLASS_SUBWAVE, ND_CLASS_WORKGROUP, ND_CLASS_GRID = -1, 0, 1, 2
 

@@ -39,6 +39,8 @@ struct Plan {
            total = 0;
     int64_t bit_words = 0;
     size_t hist_bytes = 0;     // largest histogram over the steps' sort plans
+    int64_t state_len = 0;     // multi-dimensional walk: vertices in the samples' root sets
+    size_t o_state = 0, o_transits = 0;
 };
 
 int64_t step_fanout(int app, const nd_params* p, int i) {
@@ -64,7 +66,7 @@ int check_params(const Graph& g, int app, const nd_params* p, int64_t num_roots,
                   sizeof(nd_params));
         return ND_ERR_BAD_ARGUMENT;
     }
-    if (app < ND_DEEPWALK || app > ND_LAYER) {
+    if (app < ND_DEEPWALK || app > ND_MULTIRW) {
         set_error("unknown app %d", app);
         return ND_ERR_BAD_ARGUMENT;
     }
@@ -76,7 +78,7 @@ int check_params(const Graph& g, int app, const nd_params* p, int64_t num_roots,
         set_error("num_roots is negative");
         return ND_ERR_BAD_ARGUMENT;
     }
-    const bool walk = app == ND_DEEPWALK || app == ND_PPR || app == ND_NODE2VEC;
+    const bool walk = app == ND_DEEPWALK || app == ND_PPR || app == ND_NODE2VEC || app == ND_MULTIRW;
     if (p->num_steps < 1 || p->num_steps > (walk ? ND_MAX_WALK_STEPS : ND_MAX_FANOUT_STEPS)) {
         set_error("num_steps %d outside [1, %d]", p->num_steps,
                   walk ? ND_MAX_WALK_STEPS : ND_MAX_FANOUT_STEPS);
@@ -86,8 +88,8 @@ int check_params(const Graph& g, int app, const nd_params* p, int64_t num_roots,
         set_error("use_weights set but the graph was created without weights");
         return ND_ERR_NO_WEIGHTS;
     }
-    if (p->use_weights && !walk) {
-        set_error("use_weights applies to the random walks only");
+    if (p->use_weights && (!walk || app == ND_MULTIRW)) {
+        set_error("use_weights applies to DeepWalk, PPR and node2vec only");
         return ND_ERR_BAD_ARGUMENT;
     }
     if (p->sched_force_class < ND_CLASS_AUTO || p->sched_force_class > ND_CLASS_GRID ||
@@ -138,6 +140,17 @@ int check_params(const Graph& g, int app, const nd_params* p, int64_t num_roots,
             return ND_ERR_TOO_LARGE;
         }
         pl->S = num_roots / p->roots_per_sample;
+    } else if (app == ND_MULTIRW) {
+        if (p->roots_per_sample < 1 || p->roots_per_sample > ND_MAX_LAYER_TRANSITS) {
+            set_error("roots_per_sample outside [1, %d]", ND_MAX_LAYER_TRANSITS);
+            return ND_ERR_BAD_ARGUMENT;
+        }
+        if (num_roots % p->roots_per_sample) {
+            set_error("num_roots is not a multiple of roots_per_sample");
+            return ND_ERR_BAD_ARGUMENT;
+        }
+        pl->S = num_roots / p->roots_per_sample;
+        pl->state_len = num_roots;
     } else {
         pl->S = num_roots;
     }
@@ -181,6 +194,10 @@ void layout(Plan* pl, int64_t V) {
     size_t o = sizeof(WsHeader);
     pl->o_ctl = o;
     o = align_up(o + sizeof(StepCtl) * (size_t)pl->k);
+    if (pl->app == ND_MULTIRW) {
+        pl->o_state = o; o = align_up(o + (size_t)(pl->state_len > 0 ? pl->state_len : 1) * 4);
+        pl->o_transits = o; o = align_up(o + (size_t)(pl->S > 0 ? pl->S : 1) * 4);
+    }
     if (pl->mode == ND_MODE_TRANSIT_PARALLEL && !pl->collective) {
         const size_t n = (size_t)(pl->max_slots > 0 ? pl->max_slots : 1);
         pl->o_keysA = o; o = align_up(o + n * 4);
@@ -492,11 +509,27 @@ int nd_sample(const nd_graph* h, int app, const nd_params* params, const int32_t
         a.b_max = a.b_far > a.b_max ? a.b_far : a.b_max;
     }
 
+    const bool multirw = app == ND_MULTIRW;
+    int32_t* mrw_state = (int32_t*)(ws + pl.o_state);
+    int32_t* mrw_transits = (int32_t*)(ws + pl.o_transits);
+    const uint32_t mrw_R = (uint32_t)params->roots_per_sample;
+    if (multirw) {
+        rc = multirw_init(g, roots_dev, pl.state_len, mrw_state, &hdr->status, stream);
+        if (rc != ND_OK) return rc;
+    }
+
     for (int i = 0; i < pl.k; ++i) {
         int64_t n_slots, n_out;
         step_shape(pl, params, i, &n_slots, &n_out);
         const int32_t m = (int32_t)step_fanout(app, params, i);
         const int32_t* src = i == 0 ? roots_dev : step_out_dev[i - 1];
+        if (multirw) {  // the step's transits are the picked roots, not the previous output
+            n_slots = pl.S;
+            rc = multirw_select(mrw_state, pl.S, mrw_R, seed, a.sample_base, (uint32_t)i, mrw_transits,
+                                stream);
+            if (rc != ND_OK) return rc;
+            src = mrw_transits;
+        }
         a.step = (uint32_t)i;
         a.m = (uint32_t)m;
         a.div_m = make_fastdiv((uint32_t)m);
@@ -506,8 +539,13 @@ int nd_sample(const nd_graph* h, int app, const nd_params* params, const int32_t
         a.out = step_out_dev[i];
         if (pl.mode == ND_MODE_SAMPLE_PARALLEL) {
             mark_phase(ND_PHASE_SAMPLE_SP, stream);
-            rc = sample_step_sp(g, draw, a, src, n_slots, i == 0, &hdr->status, stream);
+            rc = sample_step_sp(g, draw, a, src, n_slots, i == 0 && !multirw, &hdr->status, stream);
             if (rc != ND_OK) return rc;
+            if (multirw) {
+                rc = multirw_update(mrw_state, pl.S, mrw_R, seed, a.sample_base, (uint32_t)i,
+                                    step_out_dev[i], stream);
+                if (rc != ND_OK) return rc;
+            }
             continue;
         }
         SchedParams sp{m, pl.sub_max, pl.wg_max, params->sched_force_class};
@@ -517,7 +555,8 @@ int nd_sample(const nd_graph* h, int app, const nd_params* params, const int32_t
         rc = sort_pairs(src, n_slots, (int32_t)g.V, plan, (int32_t*)(ws + pl.o_keysA),
                         (int32_t*)(ws + pl.o_valsA), (int32_t*)(ws + pl.o_keysB),
                         (int32_t*)(ws + pl.o_valsB), (uint32_t*)(ws + pl.o_hist), ctl + i,
-                        step_out_dev[i], m, i == 0 ? &hdr->status : nullptr, &keys, &vals, stream);
+                        step_out_dev[i], m, (i == 0 && !multirw) ? &hdr->status : nullptr, &keys, &vals,
+                        stream);
         if (rc != ND_OK) return rc;
         int32_t* g_key = (int32_t*)(ws + pl.o_gkey);
         int32_t* g_start = (int32_t*)(ws + pl.o_gstart);
@@ -556,6 +595,11 @@ int nd_sample(const nd_graph* h, int app, const nd_params* params, const int32_t
         t.cap_chunks = pl.cap_chunks;
         rc = sample_step_tp(g, draw, a, sp, t, stream);
         if (rc != ND_OK) return rc;
+        if (multirw) {
+            rc = multirw_update(mrw_state, pl.S, mrw_R, seed, a.sample_base, (uint32_t)i,
+                                step_out_dev[i], stream);
+            if (rc != ND_OK) return rc;
+        }
     }
     mark_phase(ND_PHASE_NONE, stream);
     return ND_OK;

@@ -47,6 +47,17 @@ int sample_step_tp(const Graph& gr, int draw, const DrawArgs& a, const SchedPara
 int sample_step_sp(const Graph& gr, int draw, const DrawArgs& a, const int32_t* src, int64_t n_slots,
                    int check_roots, uint32_t* status, hipStream_t stream);
 
+// Multi-dimensional walk (Section 3): the sample's root set lives in `state` (S * R vertices).
+// init copies the roots (out-of-range ones become NULL and are reported), select writes the
+// step's transit of every sample (the root picked with R2 of the step's generator call) and
+// update puts the vertex the step added in the picked root's place.
+int multirw_init(const Graph& gr, const int32_t* roots, int64_t n, int32_t* state, uint32_t* status,
+                 hipStream_t stream);
+int multirw_select(const int32_t* state, int64_t S, uint32_t R, uint64_t seed, uint32_t sample_base,
+                   uint32_t step, int32_t* transits, hipStream_t stream);
+int multirw_update(int32_t* state, int64_t S, uint32_t R, uint64_t seed, uint32_t sample_base,
+                   uint32_t step, const int32_t* added, hipStream_t stream);
+
 // Layer (collective) sampling: one step for all samples.
 struct LayerArgs {
     uint64_t seed;

@@ -446,7 +446,67 @@ int launch_sp(const Graph& gr, const DrawArgs& a, const int32_t* src, int64_t n_
     return ND_OK;
 }
 
+// ---------------------------------------------------------------- multi-dimensional walk
+__global__ __launch_bounds__(256) void mrw_init_kernel(const int32_t* __restrict__ roots, int64_t n,
+                                                       int32_t V, int32_t* __restrict__ state,
+                                                       uint32_t* __restrict__ status) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    int32_t v = roots[i];
+    if (v >= V || v < ND_NULL_VERTEX) {
+        atomicOr(status, 1u);
+        v = ND_NULL_VERTEX;
+    }
+    state[i] = v;
+}
+
+// UPDATE = false: transits[s] = the picked root.  UPDATE = true: the picked root becomes added[s].
+template <bool UPDATE>
+__global__ __launch_bounds__(256) void mrw_pick_kernel(int32_t* __restrict__ state, int64_t S,
+                                                       uint32_t R, uint64_t seed, uint32_t sample_base,
+                                                       uint32_t step, int32_t* __restrict__ transits,
+                                                       const int32_t* __restrict__ added) {
+    const int64_t s = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (s >= S) return;
+    const Rand4 r = draw4(seed, sample_base + (uint32_t)s, 0u, step, 0u);
+    const uint32_t pick = mulhi32(r.r2, R);
+    if (UPDATE) {
+        const int32_t v = added[s];
+        if (v >= 0) state[s * (int64_t)R + pick] = v;
+    } else {
+        transits[s] = state[s * (int64_t)R + pick];
+    }
+}
+
 }  // namespace
+
+int multirw_init(const Graph& gr, const int32_t* roots, int64_t n, int32_t* state, uint32_t* status,
+                 hipStream_t stream) {
+    if (n == 0) return ND_OK;
+    hipLaunchKernelGGL(mrw_init_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, roots,
+                       n, (int32_t)gr.V, state, status);
+    ND_HIP_CHECK(hipGetLastError());
+    return ND_OK;
+}
+
+int multirw_select(const int32_t* state, int64_t S, uint32_t R, uint64_t seed, uint32_t sample_base,
+                   uint32_t step, int32_t* transits, hipStream_t stream) {
+    if (S == 0) return ND_OK;
+    hipLaunchKernelGGL(mrw_pick_kernel<false>, dim3((unsigned)((S + 255) / 256)), dim3(256), 0, stream,
+                       const_cast<int32_t*>(state), S, R, seed, sample_base, step, transits,
+                       (const int32_t*)nullptr);
+    ND_HIP_CHECK(hipGetLastError());
+    return ND_OK;
+}
+
+int multirw_update(int32_t* state, int64_t S, uint32_t R, uint64_t seed, uint32_t sample_base,
+                   uint32_t step, const int32_t* added, hipStream_t stream) {
+    if (S == 0) return ND_OK;
+    hipLaunchKernelGGL(mrw_pick_kernel<true>, dim3((unsigned)((S + 255) / 256)), dim3(256), 0, stream,
+                       state, S, R, seed, sample_base, step, (int32_t*)nullptr, added);
+    ND_HIP_CHECK(hipGetLastError());
+    return ND_OK;
+}
 
 #define ND_DISPATCH(DRAWV, CALL)                                                         \
     do {                                                                                 \

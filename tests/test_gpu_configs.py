@@ -152,6 +152,21 @@ def test_config5_khop_and_deepwalk():
         alive = nxt
 
 
+def test_multirw_on_the_large_graph():
+    """Multi-dimensional walk with the paper's parameters (100 roots per sample, length 100) on the
+    scale-22 R-MAT graph, 40,000 samples; windows of samples against the oracle."""
+    g = inputs.config5_graph()
+    dg = B.nd_graph_create(g.row_offsets, g.col_indices)
+    og = oracle.OracleGraph(g.row_offsets, g.col_indices)
+    S, R = 40000, 100
+    roots = inputs.permutation(g.V, 7)[:S * R].copy()
+    s, out = _run(dg, B.ND_MULTIRW, roots, 7, num_steps=100, roots_per_sample=R)
+    for a, b in _windows(S, 300, 3, 57):
+        want = oracle.multirw(og, roots[a * R:b * R], R, 100, seed=7, sample_id_base=a)
+        for i in range(100):
+            assert np.array_equal(out[i][a:b].cpu().numpy(), want[i]), f"multirw step {i} window {a}"
+
+
 def test_largest_slot_count_a_call_accepts():
     """k-hop whose last step has 2,097,152,000 slots (the ABI's limit is 2^31 - 1 per step):
     every 32-bit index in the kernels is exercised near its top."""

@@ -156,6 +156,38 @@ def test_node2vec_classes(small_w):
         assert (stats[1:, 3] > 0).all() and (stats[1:, 4] > 0).all()
 
 
+# ----------------------------------------------------------------------------- multi-dimensional walk
+@pytest.mark.parametrize("mode", [SP, TP])
+@pytest.mark.parametrize("R,S", [(1, 5000), (4, 9001), (100, 700)])
+def test_multirw(small, mode, R, S):
+    dg, og = device_graph(small)
+    roots = _roots(small, R * S, 17)
+    roots[::97] = -1                                        # some empty root slots
+    want = oracle.multirw(og, roots, R, 25, seed=77)
+    got, _ = gpu_sample(dg, B.ND_MULTIRW, roots, 77, num_steps=25, roots_per_sample=R, mode=mode)
+    assert_steps_equal(got, list(want), f"multirw R={R}")
+
+
+def test_multirw_classes_base_and_bad_roots(small64):
+    dg, og = device_graph(small64)
+    roots = _roots(small64, 8 * 4000, 18)
+    want = oracle.multirw(og, roots, 8, 12, seed=78)
+    got, stats = gpu_sample(dg, B.ND_MULTIRW, roots[8 * 1000:], 78, num_steps=12, roots_per_sample=8,
+                            sample_id_base=1000, sched_sub_max=2, sched_wg_max=8)
+    assert_steps_equal(got, [w[1000:] for w in want], "multirw base + classes")
+    assert (stats[:, 3] > 0).all() and (stats[:, 4] > 0).all()
+    roots[5] = small64.V + 3
+    want = oracle.multirw(og, roots, 8, 6, seed=79)
+    got, _ = gpu_sample(dg, B.ND_MULTIRW, roots, 79, check_status=False, num_steps=6, roots_per_sample=8)
+    assert_steps_equal(got, list(want), "multirw bad root")
+    p = B.nd_params_init(num_steps=6, roots_per_sample=8)
+    s = B.Sampler(dg, B.ND_MULTIRW, p, roots.size)
+    s.run(torch.as_tensor(roots, device="cuda:0"), 79)
+    with pytest.raises(B.NdError) as e:
+        s.status()
+    assert e.value.code == B.ND_ERR_BAD_ROOT
+
+
 # ----------------------------------------------------------------------------- k-hop
 @pytest.mark.parametrize("mode", [SP, TP])
 @pytest.mark.parametrize("fanout", [[25, 10], [3], [2, 3, 4], [1, 1, 1, 1]])
