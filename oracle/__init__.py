@@ -67,6 +67,8 @@ def _load():
         L.ndo_multirw.argtypes = [vp, i32, vp, i64, u64, u64, i32, vp]
         L.ndo_khop.restype = ctypes.c_int
         L.ndo_khop.argtypes = [vp, vp, i32, vp, i64, u64, u64, vp]
+        L.ndo_khop_unique.restype = ctypes.c_int
+        L.ndo_khop_unique.argtypes = [vp, vp, i32, i32, vp, i64, u64, u64, vp]
         L.ndo_layer.restype = ctypes.c_int
         L.ndo_layer.argtypes = [vp, i32, vp, i32, vp, i64, u64, u64, vp]
         _lib = L
@@ -174,15 +176,20 @@ def multirw(g: OracleGraph, roots, roots_per_sample: int, length: int, seed: int
     return out
 
 
-def khop(g: OracleGraph, roots, fanout, seed: int, sample_id_base: int = 0):
-    """Returns a list with one int32 [S, W_i] array per step."""
+def khop(g: OracleGraph, roots, fanout, seed: int, sample_id_base: int = 0, unique_rounds: int = 0):
+    """Returns a list with one int32 [S, W_i] array per step.  unique_rounds > 0: no vertex
+    twice within a sample and step (that many draw rounds per slot)."""
     r = _roots(roots)
     f = np.ascontiguousarray(fanout, dtype=np.int32)
     S = r.shape[0]
     widths = np.cumprod(f.astype(np.int64))
     out = np.empty(int(S * widths.sum()), dtype=np.int32)
-    _check(_load().ndo_khop(g._h, f.ctypes.data, f.shape[0], r.ctypes.data, S, sample_id_base, seed,
-                            out.ctypes.data), "khop")
+    if unique_rounds > 0:
+        _check(_load().ndo_khop_unique(g._h, f.ctypes.data, f.shape[0], unique_rounds, r.ctypes.data, S,
+                                       sample_id_base, seed, out.ctypes.data), "khop_unique")
+    else:
+        _check(_load().ndo_khop(g._h, f.ctypes.data, f.shape[0], r.ctypes.data, S, sample_id_base,
+                                seed, out.ctypes.data), "khop")
     res, base = [], 0
     for W in widths:
         res.append(out[base:base + S * int(W)].reshape(S, int(W)))

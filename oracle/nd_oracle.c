@@ -383,6 +383,64 @@ int ndo_khop(const ndo_graph* g, const int32_t* fanout, int32_t k, const int32_t
 }
 
 /* ------------------------------------------------------------------------ */
+/* k-hop sampling with unique neighbours (Section 6.3): within one sample and */
+/* one step no vertex may appear twice.  Round 0 is the ordinary step (every  */
+/* slot with a live parent draws, attempt 0).  Duplicates are then removed:   */
+/* among slots holding the same vertex the lowest slot keeps it.  The slots   */
+/* that lost draw again from their own parent (attempt 1, 2, ... - the        */
+/* paper's sample-parallel refill), and a new candidate is accepted only if   */
+/* no slot already holds its vertex, lower slots first.  After `rounds`       */
+/* rounds a slot that is still open gets NULL.  Layout as ndo_khop.           */
+/* ------------------------------------------------------------------------ */
+int ndo_khop_unique(const ndo_graph* g, const int32_t* fanout, int32_t k, int32_t rounds,
+                    const int32_t* roots, int64_t S, uint64_t sample_id_base, uint64_t seed,
+                    int32_t* out) {
+    if (rounds < 1) return -2;
+    int64_t step_base = 0, W_prev = 1;
+    const int32_t* prev = NULL;
+    for (int32_t i = 0; i < k; ++i) {
+        const int64_t m = fanout[i];
+        if (m < 1) return -2;
+        const int64_t W = W_prev * m;
+        int32_t* cur = out + step_base;
+        char* open = (char*)malloc((size_t)W);
+        if (!open) return -5;
+        for (int64_t s = 0; s < S; ++s) {
+            int32_t* row = cur + s * W;
+            for (int64_t j = 0; j < W; ++j) {
+                const int32_t parent = i == 0 ? (valid_vertex(g, roots[s]) ? roots[s] : NDO_NULL)
+                                              : prev[s * W_prev + j / m];
+                row[j] = NDO_NULL;
+                open[j] = parent != NDO_NULL && degree(g, parent) > 0;
+            }
+            for (int32_t r = 0; r < rounds; ++r) {
+                for (int64_t j = 0; j < W; ++j) {  /* lower slots first */
+                    if (!open[j]) continue;
+                    const int32_t parent = i == 0 ? roots[s] : prev[s * W_prev + j / m];
+                    uint32_t rn[4];
+                    draw4(seed, (uint32_t)(sample_id_base + (uint64_t)s), (uint32_t)j, (uint32_t)i,
+                          (uint32_t)r, rn);
+                    const int32_t cand =
+                        g->col[g->off[parent] + ndo_uniform_index(rn[0], (uint32_t)degree(g, parent))];
+                    int taken = 0;
+                    for (int64_t q = 0; q < W && !taken; ++q)
+                        if (row[q] == cand) taken = 1;
+                    if (!taken) {
+                        row[j] = cand;
+                        open[j] = 0;
+                    }
+                }
+            }
+        }
+        free(open);
+        prev = cur;
+        step_base += S * W;
+        W_prev = W;
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------ */
 /* Layer sampling with LADIES-style importance weights (Section 3, "Layer    */
 /* Sampling"; Section 4.2, "Importance Sampling"): collective transit        */
 /* sampling.  At step i a sample draws fanout[i] vertices from the combined  */

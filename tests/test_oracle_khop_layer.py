@@ -216,3 +216,92 @@ def test_layer_sample_id_base():
     full = oracle.layer(og, roots, 16, [32, 32], seed=5)
     part = oracle.layer(og, roots[3 * 16:6 * 16], 16, [32, 32], seed=5, sample_id_base=3)
     assert (full[0][3:6] == part[0]).all() and (full[1][3:6] == part[1]).all()
+
+
+# ----------------------------------------------------------------------------- unique neighbours
+
+def _rows_are_unique_neighbours(g, roots, out, fanout):
+    off = g.row_offsets
+    parent = np.asarray(roots).reshape(-1, 1)
+    for i, m in enumerate(fanout):
+        o = out[i]
+        for s in range(o.shape[0]):
+            live = o[s][o[s] >= 0]
+            assert len(set(live.tolist())) == live.size                 # no vertex twice
+            for j in range(o.shape[1]):
+                p = int(parent[s, j // m])
+                if o[s, j] >= 0:
+                    assert o[s, j] in g.col_indices[off[p]:off[p + 1]]  # a neighbour of its parent
+        parent = o
+
+
+def test_unique_khop_invariants():
+    g = inputs.small_graph(8, 1500, seed=3)
+    og = _og(g)
+    roots = np.arange(g.V, dtype=np.int32)
+    out = oracle.khop(og, roots, [6, 4], seed=12, unique_rounds=4)
+    _rows_are_unique_neighbours(g, roots, out, [6, 4])
+
+
+def test_unique_equals_with_replacement_where_nothing_collides():
+    g = inputs.small_graph(8, 1500, seed=3)
+    og = _og(g)
+    roots = np.arange(g.V, dtype=np.int32)
+    plain = oracle.khop(og, roots, [5, 3], seed=13)
+    uniq = oracle.khop(og, roots, [5, 3], seed=13, unique_rounds=3)
+    same_rows = 0
+    for s in range(g.V):
+        live0 = plain[0][s][plain[0][s] >= 0]
+        live1 = plain[1][s][plain[1][s] >= 0]
+        if len(set(live0.tolist())) == live0.size and len(set(live1.tolist())) == live1.size:
+            assert (uniq[0][s] == plain[0][s]).all() and (uniq[1][s] == plain[1][s]).all()
+            same_rows += 1
+    assert same_rows > 20
+
+
+def test_unique_with_one_round_only_removes_duplicates():
+    # no refill: the lowest slot of every repeated vertex keeps it, the others become NULL
+    g = inputs.from_edges(5, [(0, 1), (0, 2), (0, 3), (0, 4)])
+    og = _og(g)
+    roots = np.zeros(3000, dtype=np.int32)
+    plain = oracle.khop(og, roots, [4], seed=14)[0]
+    uniq = oracle.khop(og, roots, [4], seed=14, unique_rounds=1)[0]
+    for s in range(3000):
+        seen = set()
+        for j in range(4):
+            v = int(plain[s, j])
+            assert uniq[s, j] == (v if v not in seen else -1)
+            seen.add(v)
+
+
+def test_unique_refill_is_uniform_over_the_remaining_neighbours():
+    # two slots from a vertex with five neighbours: ordered pairs of distinct neighbours, all 20 alike
+    g = inputs.from_edges(6, [(0, i) for i in range(1, 6)])
+    S = 100000
+    out = oracle.khop(_og(g), np.zeros(S, dtype=np.int32), [2], seed=15, unique_rounds=12)[0]
+    assert (out >= 1).all() and (out[:, 0] != out[:, 1]).all()
+    code = (out[:, 0] - 1) * 5 + (out[:, 1] - 1)
+    counts = np.bincount(code, minlength=25)
+    keep = np.array([a != b for a in range(5) for b in range(5)])
+    assert (counts[~keep] == 0).all()
+    assert stats.chisquare(counts[keep]).pvalue > 1e-4
+    # the refill draw of slot 1 is the generator call with the next attempt number
+    off = g.row_offsets
+    for s in range(200):
+        a = int(out[s, 0])
+        for att in range(12):
+            r0 = int(oracle.draw(15, s, 1, 0, att)[0])
+            cand = int(g.col_indices[off[0] + ((r0 * 5) >> 32)])
+            if cand != a:
+                assert out[s, 1] == cand
+                break
+
+
+def test_unique_exhausts_small_neighbourhoods():
+    # four slots from a vertex with two neighbours: both appear once, two slots stay NULL
+    g = inputs.from_edges(3, [(0, 1), (0, 2)])
+    out = oracle.khop(_og(g), np.zeros(500, dtype=np.int32), [4, 2], seed=16, unique_rounds=16)
+    for s in range(500):
+        live = sorted(int(v) for v in out[0][s] if v >= 0)
+        assert live == [1, 2]
+        assert (out[1][s] == -1).all()          # 1 and 2 have no out-edges; NULL parents give NULL

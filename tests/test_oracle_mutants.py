@@ -35,6 +35,10 @@ MUTANTS = {
     "khop_parent_index": ("parent = prev[s * W_prev + j / m];", "parent = prev[s * W_prev + j % W_prev];"),
     "khop_counter_slot": ("(uint32_t)j, (uint32_t)i, 0u, r);\n                    next = g->col[g->off[parent]",
                           "(uint32_t)(j / m), (uint32_t)i, 0u, r);\n                    next = g->col[g->off[parent]"),
+    "multirw_pick_word": ("ndo_uniform_index(r[2], (uint32_t)R)", "ndo_uniform_index(r[1], (uint32_t)R)"),
+    "multirw_root_not_replaced": ("                cur[pick] = next;\n", ""),
+    "unique_checks_lower_slots_only": ("for (int64_t q = 0; q < W && !taken; ++q)", "for (int64_t q = 0; q < j && !taken; ++q)"),
+    "unique_refill_repeats_attempt_zero": ("(uint32_t)r, rn);", "0u, rn);"),
     "layer_weight_not_squared": ("total += d * ((((uint64_t)1) << 48) / (d * d));", "total += d * ((((uint64_t)1) << 48) / d);"),
     "layer_index_ignores_lists_in_front": ("(int64_t)((x - before) / c)", "(int64_t)((x / c) % d)"),
     "layer_total_drops_first_transit": ("for (int64_t t = 0; t < n_prev; ++t) {\n                const int32_t v = transits[t];\n                if (!valid_vertex(g, v)) continue;\n                const uint64_t d = (uint64_t)degree(g, v);\n                if (d == 0) continue;\n                if (d >= (1u << 24)) return -4;",
