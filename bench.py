@@ -38,6 +38,8 @@ WORKLOADS = {
     # name: (graph builder, app, params, description)
     "c5_khop": ("config5_graph", "khop", dict(num_steps=2, fanout=[25, 10]),
                 "k-hop [25,10], every vertex a root, R-MAT scale 22 (int64 offsets)"),
+    "c5_khop_unique": ("config5_graph", "khop", dict(num_steps=2, fanout=[25, 10], unique_rounds=4),
+                       "k-hop [25,10] with unique neighbours (4 rounds), every vertex a root, R-MAT scale 22"),
     "c5_deepwalk": ("config5_graph", "deepwalk", dict(num_steps=100),
                     "DeepWalk length 100, one walk per vertex, R-MAT scale 22"),
     "c3_khop": ("config3_graph", "khop", dict(num_steps=2, fanout=[25, 10]),
@@ -192,7 +194,7 @@ def main():
             r = roots_np[:n]
             t = time.perf_counter()
             if app == B.ND_KHOP:
-                o = oracle.khop(og, r, pkw["fanout"], seed)
+                o = oracle.khop(og, r, pkw["fanout"], seed, unique_rounds=pkw.get("unique_rounds", 0))
             elif app == B.ND_DEEPWALK:
                 o = list(oracle.deepwalk(og, r, pkw["num_steps"], seed, use_weights=bool(pkw.get("use_weights", 0))))
             elif app == B.ND_PPR:

@@ -43,6 +43,7 @@ extern "C" {
 #define ND_MAX_FANOUT_STEPS 8 /* k-hop / layer steps */
 #define ND_MAX_WALK_STEPS 4096
 #define ND_MAX_LAYER_TRANSITS 4096 /* roots_per_sample and layer fanouts */
+#define ND_MAX_UNIQUE_SLOTS 2048    /* slots per sample and step with unique_rounds > 0 */
 
 typedef enum nd_status {
     ND_OK = 0,
@@ -112,7 +113,13 @@ typedef struct nd_params {
                                /* the chunk a grid-class transit is cut into (0: 8192) */
     int32_t lds_stage_policy;  /* 0: stage the adjacency list in LDS when it fits and  */
                                /* pays; 1: never stage; 2: stage whenever it fits      */
-    int32_t reserved[5];
+    int32_t unique_rounds;     /* k-hop: 0 = neighbours are drawn with replacement; r > 0 = */
+                               /* unique neighbours (Section 6.3): within a sample and step */
+                               /* no vertex appears twice; a slot that drew a vertex already */
+                               /* held by a lower slot draws again (attempt 1 .. r-1) and is */
+                               /* NULL if it never finds a free one.  Needs at most 2,048    */
+                               /* slots per sample and step.                                 */
+    int32_t reserved[4];
 } nd_params;
 
 typedef struct nd_graph nd_graph; /* opaque; owned by the library */
@@ -253,7 +260,8 @@ typedef enum nd_phase {
     ND_PHASE_SAMPLE_GRID = 6, /* unused                                             */
     ND_PHASE_SAMPLE_SP = 7,   /* sample-parallel kernel (ablation mode)             */
     ND_PHASE_LAYER = 8,       /* collective (layer) kernel                          */
-    ND_PHASE_COUNT = 9
+    ND_PHASE_UNIQUE = 9,      /* duplicate removal and refill (unique neighbours)   */
+    ND_PHASE_COUNT = 10
 } nd_phase;
 int nd_profile_enable(int on);
 int nd_profile_read(double* ms, int64_t* intervals);

@@ -33,7 +33,7 @@ EXPORTS = ["nd_params_init", "nd_graph_create", "nd_graph_destroy", "nd_graph_in
            "nd_group_by_transit", "nd_profile_enable", "nd_profile_read", "nd_last_error", "nd_version"]
 
 ND_PHASES = ["init", "fill", "sort", "group", "sample_sub", "sample_wg", "sample_grid", "sample_sp",
-             "layer"]
+             "layer", "unique"]
 
 
 class nd_params(ctypes.Structure):
@@ -54,7 +54,8 @@ class nd_params(ctypes.Structure):
         ("sched_sub_max", ctypes.c_int32),
         ("sched_wg_max", ctypes.c_int32),
         ("lds_stage_policy", ctypes.c_int32),
-        ("reserved", ctypes.c_int32 * 5),
+        ("unique_rounds", ctypes.c_int32),
+        ("reserved", ctypes.c_int32 * 4),
     ]
 
 

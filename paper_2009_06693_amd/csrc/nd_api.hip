@@ -108,6 +108,10 @@ int check_params(const Graph& g, int app, const nd_params* p, int64_t num_roots,
         set_error("sched_wg_max below sched_sub_max");
         return ND_ERR_BAD_ARGUMENT;
     }
+    if (p->unique_rounds < 0 || p->unique_rounds > 64 || (p->unique_rounds > 0 && app != ND_KHOP)) {
+        set_error("unique_rounds must be in [0, 64] and applies to k-hop only");
+        return ND_ERR_BAD_ARGUMENT;
+    }
     if (app == ND_PPR && !(p->term_prob >= 0.0 && p->term_prob <= 1.0)) {
         set_error("term_prob outside [0, 1]");
         return ND_ERR_BAD_ARGUMENT;
@@ -184,6 +188,11 @@ int check_params(const Graph& g, int app, const nd_params* p, int64_t num_roots,
         }
         if (ns > pl->max_slots) pl->max_slots = ns;
         if (no > pl->max_out) pl->max_out = no;
+        if (p->unique_rounds > 0 && pl->S > 0 && no / pl->S > ND_MAX_UNIQUE_SLOTS) {
+            set_error("unique neighbours need at most %d slots per sample and step (step %d has %lld)",
+                      ND_MAX_UNIQUE_SLOTS, i, (long long)(no / pl->S));
+            return ND_ERR_BAD_ARGUMENT;
+        }
         const size_t hb = sort_hist_bytes(make_sort_plan(ns, g.V));
         if (hb > pl->hist_bytes) pl->hist_bytes = hb;
     }
@@ -239,6 +248,23 @@ __global__ void init_header_kernel(WsHeader* h, uint32_t num_steps, StepCtl* ctl
 __global__ void publish_counts_kernel(const StepCtl* ctl, int64_t* counts) {
     counts[0] = ctl->P;
     counts[1] = ctl->U;
+}
+
+int run_unique(const Graph& g, const nd_params* params, uint64_t seed, int step, int64_t S,
+               int64_t n_slots, int64_t n_out, int32_t m, const int32_t* parents, int32_t* out,
+               hipStream_t stream) {
+    UniqueArgs u{};
+    u.seed = seed;
+    u.sample_base = (uint32_t)params->sample_id_base;
+    u.step = (uint32_t)step;
+    u.W = (uint32_t)(n_out / S);
+    u.W_prev = (uint32_t)(n_slots / S);
+    u.div_m = make_fastdiv((uint32_t)m);
+    u.rounds = params->unique_rounds;
+    u.parents = parents;
+    u.out = out;
+    mark_phase(ND_PHASE_UNIQUE, stream);
+    return unique_step(g, u, S, stream);
 }
 
 uint32_t q16(double x) {
@@ -541,6 +567,10 @@ int nd_sample(const nd_graph* h, int app, const nd_params* params, const int32_t
             mark_phase(ND_PHASE_SAMPLE_SP, stream);
             rc = sample_step_sp(g, draw, a, src, n_slots, i == 0 && !multirw, &hdr->status, stream);
             if (rc != ND_OK) return rc;
+            if (params->unique_rounds > 0) {
+                rc = run_unique(g, params, seed, i, pl.S, n_slots, n_out, m, src, step_out_dev[i], stream);
+                if (rc != ND_OK) return rc;
+            }
             if (multirw) {
                 rc = multirw_update(mrw_state, pl.S, mrw_R, seed, a.sample_base, (uint32_t)i,
                                     step_out_dev[i], stream);
@@ -595,6 +625,10 @@ int nd_sample(const nd_graph* h, int app, const nd_params* params, const int32_t
         t.cap_chunks = pl.cap_chunks;
         rc = sample_step_tp(g, draw, a, sp, t, stream);
         if (rc != ND_OK) return rc;
+        if (params->unique_rounds > 0) {
+            rc = run_unique(g, params, seed, i, pl.S, n_slots, n_out, m, src, step_out_dev[i], stream);
+            if (rc != ND_OK) return rc;
+        }
         if (multirw) {
             rc = multirw_update(mrw_state, pl.S, mrw_R, seed, a.sample_base, (uint32_t)i,
                                 step_out_dev[i], stream);

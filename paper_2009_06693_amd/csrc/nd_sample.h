@@ -58,6 +58,22 @@ int multirw_select(const int32_t* state, int64_t S, uint32_t R, uint64_t seed, u
 int multirw_update(int32_t* state, int64_t S, uint32_t R, uint64_t seed, uint32_t sample_base,
                    uint32_t step, const int32_t* added, hipStream_t stream);
 
+// Unique neighbours (Section 6.3) for one k-hop step whose first draw round has already been
+// written to `out`: per sample, duplicates are removed (the lowest slot keeps the vertex) and
+// the slots that lost draw again, sample-parallel, for rounds - 1 further attempts.
+struct UniqueArgs {
+    uint64_t seed;
+    uint32_t sample_base;
+    uint32_t step;
+    uint32_t W;               // slots per sample at this step (at most ND_MAX_UNIQUE_SLOTS)
+    uint32_t W_prev;          // slots per sample of the previous step (1 at step 0)
+    FastDiv div_m;            // slot j descends from slot j / m of the previous step
+    int32_t rounds;
+    const int32_t* parents;   // roots (step 0) or the previous step's output
+    int32_t* out;
+};
+int unique_step(const Graph& gr, const UniqueArgs& a, int64_t num_samples, hipStream_t stream);
+
 // Layer (collective) sampling: one step for all samples.
 struct LayerArgs {
     uint64_t seed;

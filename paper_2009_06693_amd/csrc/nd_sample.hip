@@ -446,6 +446,104 @@ int launch_sp(const Graph& gr, const DrawArgs& a, const int32_t* src, int64_t n_
     return ND_OK;
 }
 
+// ---------------------------------------------------------------- unique neighbours (Section 6.3)
+// One workgroup per sample.  The paper removes duplicates with a per-sample sort and scan;
+// here the vertices a sample holds live in an LDS hash table (open addressing, at least twice
+// as many buckets as slots).  Every bucket remembers the best claim on its vertex: 0 once a
+// slot holds it, otherwise the lowest slot index (+1) proposing it this round - an atomicMin,
+// so the outcome does not depend on the order in which lanes arrive.  Slots that lose draw
+// again straight from the graph (the paper's sample-parallel refill).
+template <typename OffT>
+__global__ __launch_bounds__(256) void unique_kernel(GraphView<OffT> g, UniqueArgs a) {
+    constexpr uint32_t kBuckets = 2 * ND_MAX_UNIQUE_SLOTS;
+    constexpr int kPerThread = ND_MAX_UNIQUE_SLOTS / 256;
+    __shared__ int32_t h_key[kBuckets];     // vertex of the bucket, NULL = empty
+    __shared__ uint32_t h_claim[kBuckets];  // 0 = held by a slot, else lowest proposing slot + 1
+    const uint32_t s = blockIdx.x;
+    const uint32_t W = a.W;
+    int32_t* out_row = a.out + (uint64_t)s * W;
+    uint32_t buckets = 64;                  // power of two, at least 2 W
+    while (buckets < 2u * W) buckets <<= 1;
+    const uint32_t mask = buckets - 1u;
+
+    // round 0 was drawn by the step's ordinary kernels: every vertex in the row is a candidate
+    int32_t cand[kPerThread];               // candidate of my slot t (NULL: nothing to place)
+    int32_t held[kPerThread];               // what my slot t ends up holding
+    int any_candidate = 0;
+#pragma unroll
+    for (int t = 0; t < kPerThread; ++t) {
+        const uint32_t j = threadIdx.x + (uint32_t)t * 256u;
+        cand[t] = j < W ? out_row[j] : ND_NULL_VERTEX;
+        held[t] = ND_NULL_VERTEX;
+        any_candidate |= cand[t] >= 0 ? 1 : 0;
+    }
+    if (!__syncthreads_or(any_candidate)) return;  // uniform: a sample without live parents is done
+    for (uint32_t b = threadIdx.x; b < buckets; b += 256u) {
+        h_key[b] = ND_NULL_VERTEX;
+        h_claim[b] = 0xFFFFFFFFu;
+    }
+    __syncthreads();
+
+    for (int32_t r = 0;; ++r) {
+        uint32_t where[kPerThread];
+#pragma unroll
+        for (int t = 0; t < kPerThread; ++t) {
+            if (cand[t] < 0) continue;
+            const uint32_t j = threadIdx.x + (uint32_t)t * 256u;
+            uint32_t b = ((uint32_t)cand[t] * 2654435761u) & mask;
+            // the table never holds more than W distinct vertices (every proposed vertex is held
+            // by the end of its round) in at least 2 W buckets, so a free or matching bucket is
+            // found long before the probe bound
+            for (uint32_t probe = 0; probe < buckets; ++probe) {
+                const int32_t old = atomicCAS(&h_key[b], ND_NULL_VERTEX, cand[t]);
+                if (old == ND_NULL_VERTEX || old == cand[t]) break;
+                b = (b + 1u) & mask;
+            }
+            atomicMin(&h_claim[b], j + 1u);
+            where[t] = b;
+        }
+        __syncthreads();
+        int any_open = 0;
+        bool won[kPerThread];
+#pragma unroll
+        for (int t = 0; t < kPerThread; ++t) {
+            won[t] = false;
+            if (cand[t] < 0) continue;
+            const uint32_t j = threadIdx.x + (uint32_t)t * 256u;
+            if (h_claim[where[t]] == j + 1u) {
+                held[t] = cand[t];
+                cand[t] = ND_NULL_VERTEX;   // placed
+                won[t] = true;
+            } else {
+                any_open = 1;               // draws again
+            }
+        }
+        __syncthreads();                    // every claim has been read
+        // a winner marks its bucket as held: whoever proposes that vertex later loses
+#pragma unroll
+        for (int t = 0; t < kPerThread; ++t)
+            if (won[t]) h_claim[where[t]] = 0u;
+        // uniform exit: nobody left open, or the rounds are used up
+        if (!__syncthreads_or(any_open) || r + 1 >= a.rounds) break;
+#pragma unroll
+        for (int t = 0; t < kPerThread; ++t) {
+            if (cand[t] < 0) continue;
+            const uint32_t j = threadIdx.x + (uint32_t)t * 256u;
+            const uint32_t pj = fastdiv(j, a.div_m);
+            const int32_t v = a.parents[(uint64_t)s * a.W_prev + pj];   // live: it drew in round 0
+            const uint64_t rs = (uint64_t)g.off[v];
+            const uint32_t deg = (uint32_t)((uint64_t)g.off[v + 1] - rs);
+            const Rand4 rn = draw4(a.seed, a.sample_base + s, j, a.step, (uint32_t)(r + 1));
+            cand[t] = g.col[rs + mulhi32(rn.r0, deg)];
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < kPerThread; ++t) {
+        const uint32_t j = threadIdx.x + (uint32_t)t * 256u;
+        if (j < W) out_row[j] = held[t];
+    }
+}
+
 // ---------------------------------------------------------------- multi-dimensional walk
 __global__ __launch_bounds__(256) void mrw_init_kernel(const int32_t* __restrict__ roots, int64_t n,
                                                        int32_t V, int32_t* __restrict__ state,
@@ -479,6 +577,18 @@ __global__ __launch_bounds__(256) void mrw_pick_kernel(int32_t* __restrict__ sta
 }
 
 }  // namespace
+
+int unique_step(const Graph& gr, const UniqueArgs& a, int64_t num_samples, hipStream_t stream) {
+    if (num_samples == 0) return ND_OK;
+    if (gr.off64)
+        hipLaunchKernelGGL(unique_kernel<int64_t>, dim3((unsigned)num_samples), dim3(256), 0, stream,
+                           view_of<int64_t>(gr), a);
+    else
+        hipLaunchKernelGGL(unique_kernel<int32_t>, dim3((unsigned)num_samples), dim3(256), 0, stream,
+                           view_of<int32_t>(gr), a);
+    ND_HIP_CHECK(hipGetLastError());
+    return ND_OK;
+}
 
 int multirw_init(const Graph& gr, const int32_t* roots, int64_t n, int32_t* state, uint32_t* status,
                  hipStream_t stream) {

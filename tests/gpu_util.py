@@ -31,6 +31,7 @@ def gpu_sample(dg, app, roots, seed, check_status=True, **params):
         s.status()
     res = [o.cpu().numpy().copy() for o in out]
     stats = s.stats() if p.mode == B.ND_MODE_TRANSIT_PARALLEL and app != B.ND_LAYER else None
+    del s
     return res, stats
 
 

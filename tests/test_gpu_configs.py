@@ -152,6 +152,25 @@ def test_config5_khop_and_deepwalk():
         alive = nxt
 
 
+def test_unique_khop_on_the_large_graph():
+    """GraphSAGE fanouts with unique neighbours (Section 6.3) from every vertex of the scale-22 graph."""
+    g = inputs.config5_graph()
+    dg = B.nd_graph_create(g.row_offsets, g.col_indices)
+    og = oracle.OracleGraph(g.row_offsets, g.col_indices)
+    roots = inputs.all_vertices_roots(g)
+    s, out = _run(dg, B.ND_KHOP, roots, 8, num_steps=2, fanout=[25, 10], unique_rounds=4)
+    for a, b in _windows(g.V, 200, 4, 58):
+        want = oracle.khop(og, roots[a:b], [25, 10], seed=8, sample_id_base=a, unique_rounds=4)
+        assert np.array_equal(out[0][a * 25:b * 25].cpu().numpy(), want[0].reshape(-1))
+        assert np.array_equal(out[1][a * 250:b * 250].cpu().numpy(), want[1].reshape(-1))
+    # no vertex twice within a sample and step, checked on the whole output
+    for i, W in ((0, 25), (1, 250)):
+        rows = out[i].view(-1, W)[:200000].to(torch.int64)
+        srt, _ = torch.sort(rows, dim=1)
+        dup = (srt[:, 1:] == srt[:, :-1]) & (srt[:, 1:] >= 0)
+        assert not bool(dup.any())
+
+
 def test_multirw_on_the_large_graph():
     """Multi-dimensional walk with the paper's parameters (100 roots per sample, length 100) on the
     scale-22 R-MAT graph, 40,000 samples; windows of samples against the oracle."""

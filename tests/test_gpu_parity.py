@@ -222,6 +222,35 @@ def test_khop_split_over_calls(small):
         assert np.array_equal(np.concatenate([a[i], b[i]]), want[i].reshape(-1))
 
 
+# ----------------------------------------------------------------------------- unique neighbours
+@pytest.mark.parametrize("mode", [SP, TP])
+@pytest.mark.parametrize("fanout,rounds", [([25, 10], 4), ([6, 4], 1), ([3, 3, 3], 8), ([2048], 3),
+                                           ([40, 50], 2)])
+def test_khop_unique(small, mode, fanout, rounds):
+    dg, og = device_graph(small)
+    roots = np.arange(small.V, dtype=np.int32)[: 300 if max(np.cumprod(fanout)) > 1000 else small.V]
+    want = oracle.khop(og, roots, fanout, seed=55, unique_rounds=rounds)
+    got, _ = gpu_sample(dg, B.ND_KHOP, roots, 55, num_steps=len(fanout), fanout=fanout,
+                        unique_rounds=rounds, mode=mode)
+    assert_steps_equal(got, want, f"unique khop {fanout} rounds {rounds}")
+    for o, w in zip(got, want):                              # and the point of it: no repeats
+        rows = o.reshape(w.shape)
+        for r in rows[:50]:
+            live = r[r >= 0]
+            assert np.unique(live).size == live.size
+
+
+def test_khop_unique_limits(small):
+    dg, _ = device_graph(small)
+    r = torch.zeros(8, dtype=torch.int32, device="cuda:0")
+    for app, kw in [(B.ND_KHOP, dict(num_steps=2, fanout=[50, 50], unique_rounds=2)),
+                    (B.ND_DEEPWALK, dict(num_steps=2, unique_rounds=2)),
+                    (B.ND_KHOP, dict(num_steps=1, fanout=[5], unique_rounds=65))]:
+        with pytest.raises(B.NdError) as e:
+            B.Sampler(dg, app, B.nd_params_init(**kw), 8)
+        assert e.value.code == B.ND_ERR_BAD_ARGUMENT
+
+
 # ----------------------------------------------------------------------------- layer
 @pytest.mark.parametrize("rps,fanout", [(64, [256, 256]), (16, [100]), (1, [7, 300, 5]), (300, [40, 4096])])
 def test_layer(small, rps, fanout):
