@@ -109,15 +109,15 @@ __global__ __launch_bounds__(kLayerThreads) void layer_kernel(GraphView<OffT> g,
 int layer_step(const Graph& gr, const LayerArgs& a, int64_t num_samples, hipStream_t stream) {
     if (num_samples == 0) return ND_OK;
     const size_t lds_bytes = (size_t)a.n_prev * 24;  // at most 96 KB of the 160 KB per CU
-    static bool attr_set = false;
-    if (!attr_set) {  // allow dynamic LDS above the default 64 KB limit
-        ND_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&layer_kernel<int64_t>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize,
-                                         ND_MAX_LAYER_TRANSITS * 24));
-        ND_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&layer_kernel<int32_t>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize,
-                                         ND_MAX_LAYER_TRANSITS * 24));
-        attr_set = true;
+    if (lds_bytes > 64 * 1024) {  // dynamic LDS above the default limit has to be allowed explicitly
+        if (gr.off64)
+            ND_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&layer_kernel<int64_t>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize,
+                                             ND_MAX_LAYER_TRANSITS * 24));
+        else
+            ND_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&layer_kernel<int32_t>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize,
+                                             ND_MAX_LAYER_TRANSITS * 24));
     }
     if (gr.off64)
         hipLaunchKernelGGL(layer_kernel<int64_t>, dim3((unsigned)num_samples), dim3(kLayerThreads),
