@@ -31,7 +31,7 @@ PHILOX_ONLY_DRAWS_PER_S = 8.0e11
 # WRITE_SIZE; scaled by the factors a 1 GiB copy kernel gives: x2.0 and x1.0), averaged over the
 # launches of one call.  Source: profiles/c5_khop_tp_rocprofv3.md.  None where not profiled.
 MEASURED_TRAFFIC_BYTES = {
-    ("c5_khop", "tp", "sample_sub"): int((466.1 + 2511.3 + 400.0 + 2681.2) / 2 * 1048576),
+    ("c5_khop", "tp", "sample_sub"): int((355.1 + 2137.3 + 406.1 + 2689.6) / 2 * 1048576),
 }
 
 WORKLOADS = {
@@ -161,12 +161,26 @@ def main():
     else:
         draws = live if dom != "sample_sp" else slots
     draws_per_launch = draws / launches[dom]
-    # Algorithmic bytes the sampling kernel must move: per draw 4 (one adjacency entry) + 4
-    # (one output entry); per pair 8 (sorted transit and slot) + two row offsets, shared by
-    # the pair's m draws.
-    m_avg = draws / max(1, sum(int(stats[i, 0]) for i in range(len(s.step_len)))) if stats is not None else 1.0
+    # Algorithmic bytes the dominant kernel must move.  Transit-parallel: per draw 4 (one
+    # adjacency entry) + 4 (one output entry); per pair 8 (sorted transit and slot) + two row
+    # offsets, shared by the pair's m draws.  Sample-parallel: 4 per output entry, 4 per live
+    # one (adjacency), and per parent slot 4 (the transit) + two row offsets if it is live.
+    # Layer: per sample and transit slot 4 + two row offsets, per draw 4 + 4.
     off_bytes = 16.0 if g.row_offsets.dtype.itemsize == 8 else 8.0
-    hbm_bytes_per_draw = 8.0 + (8.0 + off_bytes) / max(m_avg, 1.0)
+    if dom == "sample_sp":
+        parents = [int(roots.numel())] + [int(x) for x in s.step_len[:-1]]
+        live_parents = [int((roots >= 0).sum())] + [int((o >= 0).sum()) for o in out[:-1]]
+        total_bytes = 4.0 * slots + 4.0 * live + 4.0 * sum(parents) + off_bytes * sum(live_parents)
+        hbm_bytes_per_draw = total_bytes / max(1, draws)
+    elif dom == "layer":
+        rps = pkw["roots_per_sample"]
+        n_samples = int(roots.numel()) // rps
+        n_prev = [rps] + list(pkw["fanout"][:-1])
+        total_bytes = n_samples * sum(n * (4.0 + off_bytes) for n in n_prev) + 8.0 * live
+        hbm_bytes_per_draw = total_bytes / max(1, draws)
+    else:
+        m_avg = draws / max(1, sum(int(stats[i, 0]) for i in range(len(s.step_len)))) if stats is not None else 1.0
+        hbm_bytes_per_draw = 8.0 + (8.0 + off_bytes) / max(m_avg, 1.0)
     hbm_gbs = draws_per_launch * hbm_bytes_per_draw / (avg_launch_ms * 1e-3) / 1e9
     draws_per_s = draws_per_launch / (avg_launch_ms * 1e-3)
     roofline = {

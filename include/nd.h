@@ -108,9 +108,11 @@ typedef struct nd_params {
                                /* that slice of the call on all roots                  */
     int32_t mode;              /* nd_mode                                              */
     int32_t sched_force_class; /* nd_sched_class; anything but AUTO is for tests       */
-    int32_t sched_sub_max;     /* largest draw count handled sub-wavefront (0: 64)     */
+    int32_t sched_sub_max;     /* largest draw count (pairs x fanout) of a transit     */
+                               /* handled lane-per-draw (0: the default, 16,384)       */
     int32_t sched_wg_max;      /* largest draw count handled by one workgroup; also    */
-                               /* the chunk a grid-class transit is cut into (0: 8192) */
+                               /* the chunk a grid-class transit is cut into           */
+                               /* (0: the default, 65,536); not below sched_sub_max    */
     int32_t lds_stage_policy;  /* 0: stage the adjacency list in LDS when it fits and  */
                                /* pays; 1: never stage; 2: stage whenever it fits      */
     int32_t unique_rounds;     /* k-hop: 0 = neighbours are drawn with replacement; r > 0 = */

@@ -31,7 +31,7 @@ struct Plan {
     int64_t S = 0;             // samples
     int64_t max_slots = 0;     // longest transit array over the steps (pair capacity)
     int64_t max_out = 0;       // longest output array
-    int32_t sub_max = 64, wg_max = 8192;
+    int32_t sub_max = 16384, wg_max = 65536;
     int64_t cap_wg = 0, cap_chunks = 0;
     // workspace offsets
     size_t o_ctl = 0, o_keysA = 0, o_valsA = 0, o_keysB = 0, o_valsB = 0, o_hist = 0, o_tiles = 0,
