@@ -71,6 +71,8 @@ def _load():
         L.ndo_khop_unique.argtypes = [vp, vp, i32, i32, vp, i64, u64, u64, vp]
         L.ndo_layer.restype = ctypes.c_int
         L.ndo_layer.argtypes = [vp, i32, vp, i32, vp, i64, u64, u64, vp]
+        L.ndo_layer_edges.restype = ctypes.c_int
+        L.ndo_layer_edges.argtypes = [vp, vp, i32, vp, i32, i64, vp, vp, i64]
         _lib = L
     return _lib
 
@@ -213,3 +215,20 @@ def layer(g: OracleGraph, roots, roots_per_sample: int, fanout, seed: int, sampl
         res.append(out[base:base + B * int(m)].reshape(B, int(m)))
         base += B * int(m)
     return res
+
+
+def layer_edges(g: OracleGraph, transits, sampled):
+    """Edges between the transits [S, n_prev] of a step and the vertices [S, m] it added.
+    Returns (row_ptr int64[S * n_prev + 1], edge_slot int32[row_ptr[-1]])."""
+    t = np.ascontiguousarray(transits, dtype=np.int32)
+    v = np.ascontiguousarray(sampled, dtype=np.int32)
+    if t.ndim != 2 or v.ndim != 2 or t.shape[0] != v.shape[0]:
+        raise ValueError("transits and sampled must be [S, n_prev] and [S, m]")
+    S, n_prev, m = t.shape[0], t.shape[1], v.shape[1]
+    row_ptr = np.empty(S * n_prev + 1, dtype=np.int64)
+    _check(_load().ndo_layer_edges(g._h, t.ctypes.data, n_prev, v.ctypes.data, m, S, row_ptr.ctypes.data,
+                                   None, 0), "layer_edges (count)")
+    edges = np.empty(int(row_ptr[-1]), dtype=np.int32)
+    _check(_load().ndo_layer_edges(g._h, t.ctypes.data, n_prev, v.ctypes.data, m, S, row_ptr.ctypes.data,
+                                   edges.ctypes.data, edges.shape[0]), "layer_edges")
+    return row_ptr, edges

@@ -507,3 +507,65 @@ int ndo_layer(const ndo_graph* g, int32_t roots_per_sample, const int32_t* fanou
     }
     return 0;
 }
+
+/* ------------------------------------------------------------------------ */
+/* Edges between consecutive layers (Section 4.2, "Importance Sampling": a   */
+/* sample records the edges between the transit vertices of a step and the   */
+/* vertices the step adds).  For sample b, transit slot t and new slot j the */
+/* edge (t, j) exists when both slots hold a vertex and sampled[b][j] is in  */
+/* the adjacency list of transits[b][t].  The result is one CSR over the     */
+/* rows (b, t): row_ptr has S*n_prev + 1 entries, edge_slot lists a row's j  */
+/* in the order of (vertex id, j), which is the order in which a walk down   */
+/* the (ascending) adjacency list meets them.  A vertex drawn into several   */
+/* slots contributes each of them.  edge_slot may be NULL to count only.     */
+/* ------------------------------------------------------------------------ */
+typedef struct { int32_t v, j; } slot_of_vertex;
+
+static int by_vertex_then_slot(const void* a, const void* b) {
+    const slot_of_vertex *x = (const slot_of_vertex*)a, *y = (const slot_of_vertex*)b;
+    if (x->v != y->v) return x->v < y->v ? -1 : 1;
+    return x->j < y->j ? -1 : (x->j > y->j);
+}
+
+int ndo_layer_edges(const ndo_graph* g, const int32_t* transits, int32_t n_prev, const int32_t* sampled,
+                    int32_t m, int64_t S, int64_t* row_ptr, int32_t* edge_slot, int64_t capacity) {
+    if (n_prev < 1 || m < 1 || S < 0) return -1;
+    slot_of_vertex* list = (slot_of_vertex*)malloc((size_t)m * sizeof(slot_of_vertex));
+    if (!list) return -2;
+    int64_t n_edges = 0;
+    for (int64_t b = 0; b < S; ++b) {
+        /* the sample's new vertices, ordered by (vertex id, slot) */
+        int32_t n_list = 0;
+        for (int32_t j = 0; j < m; ++j) {
+            const int32_t v = sampled[b * m + j];
+            if (v == NDO_NULL) continue;
+            if (!valid_vertex(g, v)) { free(list); return -3; }
+            list[n_list].v = v;
+            list[n_list].j = j;
+            ++n_list;
+        }
+        qsort(list, (size_t)n_list, sizeof(slot_of_vertex), by_vertex_then_slot);
+        for (int32_t t = 0; t < n_prev; ++t) {
+            row_ptr[b * n_prev + t] = n_edges;
+            const int32_t tv = transits[b * n_prev + t];
+            if (tv == NDO_NULL) continue;
+            if (!valid_vertex(g, tv)) { free(list); return -3; }
+            /* both lists ascend by vertex id: walk them together */
+            int32_t k = 0;
+            for (int64_t e = g->off[tv]; e < g->off[tv + 1]; ++e) {
+                const int32_t u = g->col[e];
+                while (k < n_list && list[k].v < u) ++k;
+                for (int32_t kk = k; kk < n_list && list[kk].v == u; ++kk) {
+                    if (edge_slot) {
+                        if (n_edges >= capacity) { free(list); return -4; }
+                        edge_slot[n_edges] = list[kk].j;
+                    }
+                    ++n_edges;
+                }
+            }
+        }
+    }
+    row_ptr[S * (int64_t)n_prev] = n_edges;
+    free(list);
+    return 0;
+}

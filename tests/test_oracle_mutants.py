@@ -15,7 +15,8 @@ import oracle
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "oracle", "nd_oracle.c")
-PINS = ["tests/test_oracle_primitives.py", "tests/test_oracle_walks.py", "tests/test_oracle_khop_layer.py"]
+PINS = ["tests/test_oracle_primitives.py", "tests/test_oracle_walks.py", "tests/test_oracle_khop_layer.py",
+        "tests/test_oracle_edges.py"]
 
 MUTANTS = {
     "philox_multipliers_swapped": ("(uint64_t)0xD2511F53u * c0", "(uint64_t)0xD2511F53u * c2"),
@@ -39,6 +40,15 @@ MUTANTS = {
     "multirw_root_not_replaced": ("                cur[pick] = next;\n", ""),
     "unique_checks_lower_slots_only": ("for (int64_t q = 0; q < W && !taken; ++q)", "for (int64_t q = 0; q < j && !taken; ++q)"),
     "unique_refill_repeats_attempt_zero": ("(uint32_t)r, rn);", "0u, rn);"),
+    "edges_repeated_vertex_counted_once": ("for (int32_t kk = k; kk < n_list && list[kk].v == u; ++kk) {",
+                                           "for (int32_t kk = k; kk < n_list && kk < k + 1 && list[kk].v == u; ++kk) {"),
+    "edges_slot_order_not_by_vertex": ("if (x->v != y->v) return x->v < y->v ? -1 : 1;\n    return x->j < y->j",
+                                       "if (x->v != y->v) return x->v > y->v ? -1 : 1;\n    return x->j < y->j"),
+    "edges_ties_in_falling_slot_order": ("return x->j < y->j ? -1 : (x->j > y->j);", "return x->j > y->j ? -1 : (x->j < y->j);"),
+    "edges_row_pointer_off_by_one_row": ("row_ptr[b * n_prev + t] = n_edges;\n            const int32_t tv",
+                                         "row_ptr[b * n_prev + t] = n_edges + (t > 0);\n            const int32_t tv"),
+    "edges_first_samples_list_reused": ("const int32_t v = sampled[b * m + j];\n            if (v == NDO_NULL) continue;",
+                                        "const int32_t v = sampled[j];\n            if (v == NDO_NULL) continue;"),
     "layer_weight_not_squared": ("total += d * ((((uint64_t)1) << 48) / (d * d));", "total += d * ((((uint64_t)1) << 48) / d);"),
     "layer_index_ignores_lists_in_front": ("(int64_t)((x - before) / c)", "(int64_t)((x / c) % d)"),
     "layer_total_drops_first_transit": ("for (int64_t t = 0; t < n_prev; ++t) {\n                const int32_t v = transits[t];\n                if (!valid_vertex(g, v)) continue;\n                const uint64_t d = (uint64_t)degree(g, v);\n                if (d == 0) continue;\n                if (d >= (1u << 24)) return -4;",
