@@ -57,12 +57,74 @@ WORKLOADS = {
 }
 
 
+def bench_layer_edges(args, B, inputs, torch, np):
+    """Layer sampling followed by the edges between consecutive layers (Section 4.2, importance
+    sampling): per call one nd_sample and, for each of the two steps, nd_layer_edges_count, the
+    8-byte read of the total, and nd_layer_edges_fill into a buffer of that size."""
+    g = inputs.config4_graph()
+    sys.stderr.write(f"[bench] {g.describe()}\n")
+    dg = B.nd_graph_create(g.row_offsets, g.col_indices)
+    nb, R, fan = 4096, 64, [2048, 2048]
+    roots = torch.as_tensor(inputs.permutation(g.V, 4)[:nb * R].copy(), device="cuda:0")
+    p = B.nd_params_init(num_steps=2, fanout=fan, roots_per_sample=R)
+    s = B.Sampler(dg, B.ND_LAYER, p, nb * R)
+    shapes = [(nb, R), (nb, fan[0]), (nb, fan[1])]
+    ws = [torch.empty(B.nd_layer_edges_workspace_bytes(nb, shapes[i][1]), dtype=torch.uint8, device="cuda:0")
+          for i in range(2)]
+    row_ptr = [torch.empty(nb * shapes[i][1] + 1, dtype=torch.int64, device="cuda:0") for i in range(2)]
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    t_sample = t_count = t_fill = 0.0
+    edges = [0, 0]
+    e_all0, e_all1 = ev(), ev()
+    for it in range(args.warmup + args.steps):
+        if it == args.warmup:
+            torch.cuda.synchronize()
+            t_sample = t_count = t_fill = 0.0
+            e_all0.record()
+        e = [ev() for _ in range(6)]
+        e[0].record()
+        out = s.run(roots, 1)
+        e[1].record()
+        layers = [roots.view(nb, R), out[0].view(nb, fan[0]), out[1].view(nb, fan[1])]
+        marks = []
+        for i in range(2):
+            a, b, c = ev(), ev(), ev()
+            a.record()
+            B.nd_layer_edges_count(dg, layers[i], layers[i + 1], row_ptr[i], ws[i])
+            b.record()
+            edges[i] = int(row_ptr[i][-1].item())
+            slots = torch.empty(edges[i], dtype=torch.int32, device="cuda:0")
+            b2 = ev()
+            b2.record()
+            B.nd_layer_edges_fill(dg, layers[i], layers[i + 1], row_ptr[i], slots)
+            c.record()
+            marks.append((a, b, b2, c))
+        torch.cuda.synchronize()
+        t_sample += e[0].elapsed_time(e[1])
+        for a, b, b2, c in marks:
+            t_count += a.elapsed_time(b)
+            t_fill += b2.elapsed_time(c)
+    e_all1.record()
+    torch.cuda.synchronize()
+    ms = e_all0.elapsed_time(e_all1) / args.steps
+    k = args.steps
+    print(json.dumps({
+        "metric": "edges recorded/s (layer sampling + edges between consecutive layers)",
+        "value": round(sum(edges) / (ms * 1e-3), 1), "unit": "edges/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "dtype": "int32",
+        "data": "synthetic",
+        "config": {"workload": "c4_layer_edges", "graph": g.describe(), "samples": nb, "layers": [R] + fan,
+                   "edges_per_step": edges},
+        "phase_ms_per_step": {"sample": round(t_sample / k, 4), "edges_count": round(t_count / k, 4),
+                              "edges_fill": round(t_fill / k, 4)}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c5_khop", choices=sorted(WORKLOADS) + ["copy_calib"])
+    ap.add_argument("--workload", default="c5_khop", choices=sorted(WORKLOADS) + ["copy_calib", "c4_layer_edges"])
     ap.add_argument("--mode", default="tp", choices=["tp", "sp"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
@@ -100,6 +162,8 @@ def main():
                           "ms_per_copy": round(ms, 4),
                           "copy_GBps": round(2 * n * 4 / (ms * 1e-3) / 1e9, 1)}))
         return
+    if args.workload == "c4_layer_edges":
+        return bench_layer_edges(args, B, inputs, torch, np)
     builder, app_name, pkw, desc = WORKLOADS[args.workload]
     app = {"deepwalk": B.ND_DEEPWALK, "ppr": B.ND_PPR, "node2vec": B.ND_NODE2VEC, "khop": B.ND_KHOP,
            "layer": B.ND_LAYER, "multirw": B.ND_MULTIRW}[app_name]

@@ -240,6 +240,45 @@ int nd_group_by_transit(const int32_t* transits_dev, int64_t n, int64_t V,
                         void* workspace_dev, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Edges between consecutive layers (Section 4.2, "Importance Sampling": every
+ * sample carries the adjacency matrix between the transits of a step and the
+ * vertices the step added; an edge is recorded between a new vertex and every
+ * transit that has it as a neighbour).  Works on any pair of per-sample vertex
+ * arrays, e.g. the roots and step 0, or steps i-1 and i, of a layer call.
+ *
+ *   transits_dev     device, num_samples * n_prev int32 (negative = empty slot)
+ *   sampled_dev      device, num_samples * m int32 (negative = empty slot),
+ *                    m <= ND_MAX_EDGE_SLOTS
+ *   row_ptr_dev      device, num_samples * n_prev + 1 int64: one CSR over the
+ *                    rows (sample b, transit slot t), row b * n_prev + t
+ *   edge_slot_dev    device, capacity int32: a row lists every new slot j of the
+ *                    same sample with sampled[b][j] in adj(transits[b][t]), ordered
+ *                    by (vertex id, j); a vertex held by several slots gives one
+ *                    entry per slot
+ *   workspace_dev    device scratch of nd_layer_edges_workspace_bytes bytes,
+ *                    256-byte aligned, owned by the caller
+ *
+ * nd_layer_edges_count writes row_ptr (asynchronously on hip_stream); the caller
+ * reads row_ptr[num_samples * n_prev], allocates that many entries and calls
+ * nd_layer_edges_fill with the same arguments.  Entries at or beyond capacity are
+ * not written.  A vertex outside [-1, V) counts as an empty slot and is recorded:
+ * nd_layer_edges_status waits for the stream and returns ND_ERR_BAD_ROOT then.
+ * Neither call allocates.  Errors: ND_ERR_NULL_POINTER, ND_ERR_BAD_ARGUMENT,
+ * ND_ERR_TOO_LARGE, ND_ERR_WORKSPACE, ND_ERR_HIP.
+ */
+#define ND_MAX_EDGE_SLOTS 2048
+size_t nd_layer_edges_workspace_bytes(int64_t num_samples, int32_t n_prev);
+int nd_layer_edges_count(const nd_graph* g, const int32_t* transits_dev, int32_t n_prev,
+                         const int32_t* sampled_dev, int32_t m, int64_t num_samples,
+                         int64_t* row_ptr_dev, void* workspace_dev, size_t workspace_bytes,
+                         void* hip_stream);
+int nd_layer_edges_fill(const nd_graph* g, const int32_t* transits_dev, int32_t n_prev,
+                        const int32_t* sampled_dev, int32_t m, int64_t num_samples,
+                        const int64_t* row_ptr_dev, int32_t* edge_slot_dev, int64_t capacity,
+                        void* hip_stream);
+int nd_layer_edges_status(const void* workspace_dev, void* hip_stream);
+
+/*
  * Phase timing, for measurement.  After nd_profile_enable(1) on a thread, the
  * nd_sample calls of that thread bracket every phase of every step with HIP
  * events on their stream (a few microseconds per step; no synchronisation).
@@ -254,7 +293,7 @@ int nd_group_by_transit(const int32_t* transits_dev, int64_t n, int64_t V,
 typedef enum nd_phase {
     ND_PHASE_NONE = -1,
     ND_PHASE_INIT = 0,        /* workspace header / bitmap reset                    */
-    ND_PHASE_FILL = 1,        /* NULL children of slots without a transit           */
+    ND_PHASE_FILL = 1,        /* unused (the NULL fill is part of the sort's pass 0) */
     ND_PHASE_SORT = 2,        /* transit enumeration + radix sort by transit        */
     ND_PHASE_GROUP = 3,       /* segmented scan + classification                    */
     ND_PHASE_SAMPLE_SUB = 4,  /* sub-wavefront class kernel                         */

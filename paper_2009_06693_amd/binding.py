@@ -19,6 +19,7 @@ LIB_PATH = os.environ.get("ND_LIB", os.path.join(_HERE, "libnd.so"))
 ND_MAX_FANOUT_STEPS = 8
 ND_MAX_WALK_STEPS = 4096
 ND_NULL_VERTEX = -1
+ND_MAX_EDGE_SLOTS = 2048
 
 ND_DEEPWALK, ND_PPR, ND_NODE2VEC, ND_KHOP, ND_LAYER, ND_MULTIRW = range(6)
 ND_MODE_TRANSIT_PARALLEL, ND_MODE_SAMPLE_PARALLEL = 0, 1
@@ -30,7 +31,8 @@ ND_ERR_NO_WEIGHTS, ND_ERR_WORKSPACE, ND_ERR_HIP, ND_ERR_BAD_ROOT, ND_ERR_TOO_LAR
 
 EXPORTS = ["nd_params_init", "nd_graph_create", "nd_graph_destroy", "nd_graph_info", "nd_sample_query",
            "nd_sample", "nd_sample_status", "nd_sample_stats", "nd_group_workspace_bytes",
-           "nd_group_by_transit", "nd_profile_enable", "nd_profile_read", "nd_last_error", "nd_version"]
+           "nd_group_by_transit", "nd_layer_edges_workspace_bytes", "nd_layer_edges_count",
+           "nd_layer_edges_fill", "nd_layer_edges_status", "nd_profile_enable", "nd_profile_read", "nd_last_error", "nd_version"]
 
 ND_PHASES = ["init", "fill", "sort", "group", "sample_sub", "sample_wg", "sample_grid", "sample_sp",
              "layer", "unique"]
@@ -103,6 +105,14 @@ def lib() -> ctypes.CDLL:
         L.nd_group_workspace_bytes.argtypes = [i64, i64]
         L.nd_group_by_transit.restype = ctypes.c_int
         L.nd_group_by_transit.argtypes = [vp, i64, i64, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.nd_layer_edges_workspace_bytes.restype = sz
+        L.nd_layer_edges_workspace_bytes.argtypes = [i64, i32]
+        L.nd_layer_edges_count.restype = ctypes.c_int
+        L.nd_layer_edges_count.argtypes = [vp, vp, i32, vp, i32, i64, vp, vp, sz, vp]
+        L.nd_layer_edges_fill.restype = ctypes.c_int
+        L.nd_layer_edges_fill.argtypes = [vp, vp, i32, vp, i32, i64, vp, vp, i64, vp]
+        L.nd_layer_edges_status.restype = ctypes.c_int
+        L.nd_layer_edges_status.argtypes = [vp, vp]
         L.nd_profile_enable.restype = ctypes.c_int
         L.nd_profile_enable.argtypes = [ctypes.c_int]
         L.nd_profile_read.restype = ctypes.c_int
@@ -271,6 +281,60 @@ def nd_group_by_transit(transits: torch.Tensor, V: int, stream=None):
     c = counts.cpu()
     P, U = int(c[0]), int(c[1])
     return sk[:P], sv[:P], gk[:U], gs[:U + 1], P, U
+
+
+def nd_layer_edges_workspace_bytes(num_samples: int, n_prev: int) -> int:
+    return lib().nd_layer_edges_workspace_bytes(num_samples, n_prev)
+
+
+def nd_layer_edges_count(g: Graph, transits: torch.Tensor, sampled: torch.Tensor, row_ptr: torch.Tensor,
+                         workspace: torch.Tensor, stream=None):
+    """transits [S, n_prev] and sampled [S, m], int32 on the GPU; row_ptr int64 [S * n_prev + 1]."""
+    S, n_prev, m = _edge_shapes(transits, sampled)
+    if row_ptr.dtype != torch.int64 or row_ptr.numel() < S * n_prev + 1:
+        raise TypeError("row_ptr must be int64 with S * n_prev + 1 entries")
+    _check(lib().nd_layer_edges_count(g._h, transits.data_ptr() if S else None, n_prev,
+                                      sampled.data_ptr() if S else None, m, S, row_ptr.data_ptr(),
+                                      workspace.data_ptr(), workspace.numel(), _stream_ptr(stream)))
+
+
+def nd_layer_edges_fill(g: Graph, transits: torch.Tensor, sampled: torch.Tensor, row_ptr: torch.Tensor,
+                        edge_slot: torch.Tensor, stream=None):
+    S, n_prev, m = _edge_shapes(transits, sampled)
+    if edge_slot.dtype != torch.int32:
+        raise TypeError("edge_slot must be int32")
+    _check(lib().nd_layer_edges_fill(g._h, transits.data_ptr() if S else None, n_prev,
+                                     sampled.data_ptr() if S else None, m, S, row_ptr.data_ptr(),
+                                     edge_slot.data_ptr() if edge_slot.numel() else None,
+                                     edge_slot.numel(), _stream_ptr(stream)))
+
+
+def nd_layer_edges_status(workspace: torch.Tensor, stream=None):
+    _check(lib().nd_layer_edges_status(workspace.data_ptr(), _stream_ptr(stream)))
+
+
+def _edge_shapes(transits, sampled):
+    for x in (transits, sampled):
+        if x.dtype != torch.int32 or not x.is_cuda or x.dim() != 2 or not x.is_contiguous():
+            raise TypeError("transits and sampled must be contiguous 2-D int32 CUDA tensors")
+    if transits.shape[0] != sampled.shape[0]:
+        raise ValueError("transits and sampled must hold the same number of samples")
+    return int(transits.shape[0]), int(transits.shape[1]), int(sampled.shape[1])
+
+
+def layer_edges(g: Graph, transits: torch.Tensor, sampled: torch.Tensor, stream=None):
+    """Count, size, fill: returns (row_ptr int64 [S * n_prev + 1], edge_slot int32 [row_ptr[-1]])."""
+    S, n_prev, _ = _edge_shapes(transits, sampled)
+    dev = transits.device
+    wsb = nd_layer_edges_workspace_bytes(S, n_prev)
+    ws = torch.empty(max(wsb, 256), dtype=torch.uint8, device=dev)
+    row_ptr = torch.empty(S * n_prev + 1, dtype=torch.int64, device=dev)
+    nd_layer_edges_count(g, transits, sampled, row_ptr, ws, stream)
+    nd_layer_edges_status(ws, stream)
+    total = int(row_ptr[-1].item())
+    edge_slot = torch.empty(total, dtype=torch.int32, device=dev)
+    nd_layer_edges_fill(g, transits, sampled, row_ptr, edge_slot, stream)
+    return row_ptr, edge_slot
 
 
 # ---------------------------------------------------------------------------

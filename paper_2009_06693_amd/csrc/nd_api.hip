@@ -10,6 +10,7 @@
 #include <vector>
 
 #include "nd_common.h"
+#include "nd_edges.h"
 #include "nd_sample.h"
 
 struct nd_graph {
@@ -742,6 +743,82 @@ int nd_group_by_transit(const int32_t* transits_dev, int64_t n, int64_t V,
     }
     hipLaunchKernelGGL(publish_counts_kernel, dim3(1), dim3(1), 0, stream, ctl, counts_dev);
     ND_HIP_CHECK(hipGetLastError());
+    return ND_OK;
+}
+
+static int check_edge_args(const nd_graph* g, const int32_t* transits_dev, int32_t n_prev,
+                           const int32_t* sampled_dev, int32_t m, int64_t num_samples) {
+    if (!g || !g->g || (num_samples > 0 && (!transits_dev || !sampled_dev))) {
+        set_error("a required pointer is NULL");
+        return ND_ERR_NULL_POINTER;
+    }
+    if (n_prev < 1 || m < 1 || num_samples < 0) {
+        set_error("n_prev and m must be at least 1 and num_samples not negative");
+        return ND_ERR_BAD_ARGUMENT;
+    }
+    if (m > ND_MAX_EDGE_SLOTS || num_samples * (int64_t)n_prev >= (1ll << 31) ||
+        num_samples * (int64_t)m >= (1ll << 31)) {
+        set_error("at most %d new vertices per sample, and fewer than 2^31 transit slots and new slots per call",
+                  ND_MAX_EDGE_SLOTS);
+        return ND_ERR_TOO_LARGE;
+    }
+    return ND_OK;
+}
+
+size_t nd_layer_edges_workspace_bytes(int64_t num_samples, int32_t n_prev) {
+    if (num_samples < 0 || n_prev < 1) return 0;
+    return edges_workspace_bytes(num_samples, n_prev);
+}
+
+int nd_layer_edges_count(const nd_graph* g, const int32_t* transits_dev, int32_t n_prev,
+                         const int32_t* sampled_dev, int32_t m, int64_t num_samples,
+                         int64_t* row_ptr_dev, void* workspace_dev, size_t workspace_bytes,
+                         void* hip_stream) {
+    int rc = check_edge_args(g, transits_dev, n_prev, sampled_dev, m, num_samples);
+    if (rc != ND_OK) return rc;
+    if (!row_ptr_dev || !workspace_dev) {
+        set_error("a required pointer is NULL");
+        return ND_ERR_NULL_POINTER;
+    }
+    if (workspace_bytes < edges_workspace_bytes(num_samples, n_prev) ||
+        ((uintptr_t)workspace_dev % kAlign) != 0) {
+        set_error("workspace needs %zu bytes aligned to %zu", edges_workspace_bytes(num_samples, n_prev), kAlign);
+        return ND_ERR_WORKSPACE;
+    }
+    return edges_count(*g->g, transits_dev, n_prev, sampled_dev, m, num_samples, row_ptr_dev,
+                       workspace_dev, (hipStream_t)hip_stream);
+}
+
+int nd_layer_edges_fill(const nd_graph* g, const int32_t* transits_dev, int32_t n_prev,
+                        const int32_t* sampled_dev, int32_t m, int64_t num_samples,
+                        const int64_t* row_ptr_dev, int32_t* edge_slot_dev, int64_t capacity,
+                        void* hip_stream) {
+    int rc = check_edge_args(g, transits_dev, n_prev, sampled_dev, m, num_samples);
+    if (rc != ND_OK) return rc;
+    if (!row_ptr_dev || (capacity > 0 && !edge_slot_dev)) {
+        set_error("a required pointer is NULL");
+        return ND_ERR_NULL_POINTER;
+    }
+    if (capacity < 0) {
+        set_error("capacity is negative");
+        return ND_ERR_BAD_ARGUMENT;
+    }
+    return edges_fill(*g->g, transits_dev, n_prev, sampled_dev, m, num_samples, row_ptr_dev,
+                      edge_slot_dev, capacity, (hipStream_t)hip_stream);
+}
+
+int nd_layer_edges_status(const void* workspace_dev, void* hip_stream) {
+    if (!workspace_dev) {
+        set_error("a required pointer is NULL");
+        return ND_ERR_NULL_POINTER;
+    }
+    uint32_t word = 0;
+    ND_HIP_CHECK(hipMemcpyAsync(&word, workspace_dev, 4, hipMemcpyDeviceToHost, (hipStream_t)hip_stream));
+    ND_HIP_CHECK(hipStreamSynchronize((hipStream_t)hip_stream));
+    if (word) {
+        set_error("a transit or a new vertex was outside [-1, V)");
+        return ND_ERR_BAD_ROOT;
+    }
     return ND_OK;
 }
 

@@ -125,6 +125,39 @@ def test_config4_layer():
     assert int(out[0].min()) >= 0 and int(out[1].max()) < g.V
 
 
+def test_config4_layer_edges():
+    """Edges between consecutive layers (Section 4.2, importance sampling) of the layer workload:
+    4,096 samples, 64 -> 2,048 -> 2,048 vertices; whole samples against the oracle and properties
+    of the whole result."""
+    g = inputs.config4_graph()
+    dg = B.nd_graph_create(g.row_offsets, g.col_indices)
+    og = oracle.OracleGraph(g.row_offsets, g.col_indices)
+    nb = 4096
+    roots = inputs.permutation(g.V, 4)[:nb * 64].copy()
+    s, out = _run(dg, B.ND_LAYER, roots, 4, num_steps=2, fanout=[2048, 2048], roots_per_sample=64)
+    layers = [torch.as_tensor(roots, device="cuda:0").view(nb, 64), out[0].view(nb, 2048), out[1].view(nb, 2048)]
+    for i in range(2):
+        t, v = layers[i], layers[i + 1]
+        n_prev = t.shape[1]
+        print(f"[config] layer edges step {i}", flush=True)
+        row_ptr, slots = B.layer_edges(dg, t, v)
+        torch.cuda.synchronize()
+        # every new vertex was drawn from some transit's list, so every sample has at least 2,048 edges
+        per_sample = row_ptr[n_prev::n_prev] - row_ptr[:-1:n_prev]
+        assert int(per_sample.min()) >= 2048
+        assert bool((row_ptr[1:] >= row_ptr[:-1]).all()) and int(row_ptr[0]) == 0
+        assert int(row_ptr[-1]) == slots.numel()
+        assert int(slots.min()) >= 0 and int(slots.max()) < 2048
+        for b in (0, 1234, nb - 1):
+            want_ptr, want_slots = oracle.layer_edges(og, t[b:b + 1].cpu().numpy(), v[b:b + 1].cpu().numpy())
+            got_ptr = row_ptr[b * n_prev:(b + 1) * n_prev + 1].cpu().numpy()
+            assert np.array_equal(got_ptr - got_ptr[0], want_ptr), f"row pointers of sample {b}, step {i}"
+            got = slots[int(got_ptr[0]):int(got_ptr[-1])].cpu().numpy()
+            assert np.array_equal(got, want_slots), f"edges of sample {b}, step {i}"
+        del row_ptr, slots
+        torch.cuda.empty_cache()
+
+
 def test_config5_khop_and_deepwalk():
     g = inputs.config5_graph()
     assert g.row_offsets.dtype == np.int64

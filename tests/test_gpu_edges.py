@@ -1,0 +1,99 @@
+"""GPU parity for the edges between consecutive layers (Section 4.2, importance
+sampling): the C ABI's count + fill against the oracle, entry by entry."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2009_06693_amd import binding as B
+from paper_2009_06693_amd import inputs
+
+from gpu_util import device_graph
+
+pytestmark = pytest.mark.gpu
+
+
+def _compare(g, transits, sampled):
+    dg, og = device_graph(g)
+    t = torch.as_tensor(np.ascontiguousarray(transits, dtype=np.int32), device="cuda:0")
+    v = torch.as_tensor(np.ascontiguousarray(sampled, dtype=np.int32), device="cuda:0")
+    print(f"[edges] S={t.shape[0]} n_prev={t.shape[1]} m={v.shape[1]}", flush=True)
+    row_ptr, slots = B.layer_edges(dg, t, v)
+    torch.cuda.synchronize()
+    want_ptr, want_slots = oracle.layer_edges(og, transits, sampled)
+    assert np.array_equal(row_ptr.cpu().numpy(), want_ptr)
+    assert np.array_equal(slots.cpu().numpy(), want_slots)
+    return want_ptr
+
+
+_small = inputs.small_graph()
+_small64 = inputs.small_graph(scale=9, edges=9000, seed=17, int64_offsets=True)
+
+
+@pytest.mark.parametrize("n_prev,m,S", [(1, 1, 1), (64, 64, 7), (64, 2048, 5), (2048, 2048, 3), (100, 777, 9),
+                                        (3, 65, 300), (513, 1, 4)])
+def test_edges_between_random_layers(n_prev, m, S):
+    g = _small
+    rng = np.random.default_rng(n_prev * 7919 + m)
+    transits = rng.integers(-1, g.V, (S, n_prev)).astype(np.int32)
+    # new vertices drawn from the transits' neighbourhoods so that edges are plentiful, with repeats
+    deg = np.diff(g.row_offsets)
+    pool = g.col_indices[: max(1, g.E // 3)]
+    sampled = pool[rng.integers(0, pool.size, (S, m))].astype(np.int32)
+    sampled[rng.random((S, m)) < 0.05] = -1
+    ptr = _compare(g, transits, sampled)
+    if n_prev >= 64 and m >= 64:
+        assert ptr[-1] > 0
+
+
+def test_edges_of_a_sampled_layer_call_with_int64_offsets():
+    g = _small64
+    dg, og = device_graph(g)
+    S, R = 6, 16
+    roots = inputs.permutation(g.V, 3)[:S * R].copy()
+    p = B.nd_params_init(num_steps=2, fanout=[300, 500], roots_per_sample=R)
+    r = torch.as_tensor(roots, device="cuda:0")
+    s = B.Sampler(dg, B.ND_LAYER, p, S * R)
+    out = s.run(r, 9)
+    torch.cuda.synchronize()
+    layers = [roots.reshape(S, R), out[0].cpu().numpy().reshape(S, 300), out[1].cpu().numpy().reshape(S, 500)]
+    for i in range(2):
+        ptr = _compare(g, layers[i], layers[i + 1])
+        assert ptr[-1] >= layers[i + 1].shape[1] * S   # every drawn vertex is some transit's neighbour
+
+
+def test_every_vertex_once_reads_back_the_adjacency_rows():
+    g = inputs.small_graph(scale=8, edges=2500, seed=4)
+    dg, _ = device_graph(g)
+    V = g.V
+    ids = torch.arange(V, dtype=torch.int32, device="cuda:0").reshape(1, V)
+    row_ptr, slots = B.layer_edges(dg, ids, ids.clone())
+    assert np.array_equal(row_ptr.cpu().numpy(), g.row_offsets.astype(np.int64))
+    assert np.array_equal(slots.cpu().numpy(), g.col_indices)
+
+
+def test_empty_and_error_cases():
+    g = _small
+    dg, _ = device_graph(g)
+    e = torch.empty((0, 5), dtype=torch.int32, device="cuda:0")
+    row_ptr, slots = B.layer_edges(dg, e, torch.empty((0, 9), dtype=torch.int32, device="cuda:0"))
+    assert row_ptr.cpu().tolist() == [0] and slots.numel() == 0
+    t = torch.zeros((2, 4), dtype=torch.int32, device="cuda:0")
+    with pytest.raises(B.NdError) as err:
+        B.layer_edges(dg, t, torch.zeros((2, B.ND_MAX_EDGE_SLOTS + 1), dtype=torch.int32, device="cuda:0"))
+    assert err.value.code == B.ND_ERR_TOO_LARGE
+    bad = torch.full((2, 4), g.V, dtype=torch.int32, device="cuda:0")
+    with pytest.raises(B.NdError) as err:
+        B.layer_edges(dg, bad, t)
+    assert err.value.code == B.ND_ERR_BAD_ROOT
+    # a short edge buffer is filled up to its capacity and not beyond
+    rng = np.random.default_rng(1)
+    tr = torch.as_tensor(rng.integers(0, g.V, (3, 50)).astype(np.int32), device="cuda:0")
+    sv = torch.as_tensor(g.col_indices[rng.integers(0, g.E, (3, 400))].astype(np.int32), device="cuda:0")
+    row_ptr, full = B.layer_edges(dg, tr, sv)
+    assert full.numel() > 10
+    short = torch.full((full.numel(),), -7, dtype=torch.int32, device="cuda:0")
+    B.nd_layer_edges_fill(dg, tr, sv, row_ptr, short[: full.numel() // 2])
+    torch.cuda.synchronize()
+    half = full.numel() // 2
+    assert torch.equal(short[:half], full[:half]) and bool((short[half:] == -7).all())
