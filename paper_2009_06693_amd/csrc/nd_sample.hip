@@ -453,10 +453,11 @@ int launch_sp(const Graph& gr, const DrawArgs& a, const int32_t* src, int64_t n_
 // slot holds it, otherwise the lowest slot index (+1) proposing it this round - an atomicMin,
 // so the outcome does not depend on the order in which lanes arrive.  Slots that lose draw
 // again straight from the graph (the paper's sample-parallel refill).
-template <typename OffT>
-__global__ __launch_bounds__(256) void unique_kernel(GraphView<OffT> g, UniqueArgs a) {
-    constexpr uint32_t kBuckets = 2 * ND_MAX_UNIQUE_SLOTS;
-    constexpr int kPerThread = ND_MAX_UNIQUE_SLOTS / 256;
+// The workgroup is sized to the sample: THREADS * kPerThread >= W slots, one wavefront for the
+// 25-slot first hop of GraphSAGE, 256 threads for its 250-slot second hop.
+template <typename OffT, int THREADS, int kPerThread>
+__global__ __launch_bounds__(THREADS) void unique_kernel(GraphView<OffT> g, UniqueArgs a) {
+    constexpr uint32_t kBuckets = 2 * THREADS * kPerThread;
     __shared__ int32_t h_key[kBuckets];     // vertex of the bucket, NULL = empty
     __shared__ uint32_t h_claim[kBuckets];  // 0 = held by a slot, else lowest proposing slot + 1
     const uint32_t s = blockIdx.x;
@@ -472,13 +473,13 @@ __global__ __launch_bounds__(256) void unique_kernel(GraphView<OffT> g, UniqueAr
     int any_candidate = 0;
 #pragma unroll
     for (int t = 0; t < kPerThread; ++t) {
-        const uint32_t j = threadIdx.x + (uint32_t)t * 256u;
+        const uint32_t j = threadIdx.x + (uint32_t)t * (uint32_t)THREADS;
         cand[t] = j < W ? out_row[j] : ND_NULL_VERTEX;
         held[t] = ND_NULL_VERTEX;
         any_candidate |= cand[t] >= 0 ? 1 : 0;
     }
     if (!__syncthreads_or(any_candidate)) return;  // uniform: a sample without live parents is done
-    for (uint32_t b = threadIdx.x; b < buckets; b += 256u) {
+    for (uint32_t b = threadIdx.x; b < buckets; b += (uint32_t)THREADS) {
         h_key[b] = ND_NULL_VERTEX;
         h_claim[b] = 0xFFFFFFFFu;
     }
@@ -489,7 +490,7 @@ __global__ __launch_bounds__(256) void unique_kernel(GraphView<OffT> g, UniqueAr
 #pragma unroll
         for (int t = 0; t < kPerThread; ++t) {
             if (cand[t] < 0) continue;
-            const uint32_t j = threadIdx.x + (uint32_t)t * 256u;
+            const uint32_t j = threadIdx.x + (uint32_t)t * (uint32_t)THREADS;
             uint32_t b = ((uint32_t)cand[t] * 2654435761u) & mask;
             // the table never holds more than W distinct vertices (every proposed vertex is held
             // by the end of its round) in at least 2 W buckets, so a free or matching bucket is
@@ -509,7 +510,7 @@ __global__ __launch_bounds__(256) void unique_kernel(GraphView<OffT> g, UniqueAr
         for (int t = 0; t < kPerThread; ++t) {
             won[t] = false;
             if (cand[t] < 0) continue;
-            const uint32_t j = threadIdx.x + (uint32_t)t * 256u;
+            const uint32_t j = threadIdx.x + (uint32_t)t * (uint32_t)THREADS;
             if (h_claim[where[t]] == j + 1u) {
                 held[t] = cand[t];
                 cand[t] = ND_NULL_VERTEX;   // placed
@@ -528,7 +529,7 @@ __global__ __launch_bounds__(256) void unique_kernel(GraphView<OffT> g, UniqueAr
 #pragma unroll
         for (int t = 0; t < kPerThread; ++t) {
             if (cand[t] < 0) continue;
-            const uint32_t j = threadIdx.x + (uint32_t)t * 256u;
+            const uint32_t j = threadIdx.x + (uint32_t)t * (uint32_t)THREADS;
             const uint32_t pj = fastdiv(j, a.div_m);
             const int32_t v = a.parents[(uint64_t)s * a.W_prev + pj];   // live: it drew in round 0
             const uint64_t rs = (uint64_t)g.off[v];
@@ -539,7 +540,7 @@ __global__ __launch_bounds__(256) void unique_kernel(GraphView<OffT> g, UniqueAr
     }
 #pragma unroll
     for (int t = 0; t < kPerThread; ++t) {
-        const uint32_t j = threadIdx.x + (uint32_t)t * 256u;
+        const uint32_t j = threadIdx.x + (uint32_t)t * (uint32_t)THREADS;
         if (j < W) out_row[j] = held[t];
     }
 }
@@ -580,12 +581,21 @@ __global__ __launch_bounds__(256) void mrw_pick_kernel(int32_t* __restrict__ sta
 
 int unique_step(const Graph& gr, const UniqueArgs& a, int64_t num_samples, hipStream_t stream) {
     if (num_samples == 0) return ND_OK;
-    if (gr.off64)
-        hipLaunchKernelGGL(unique_kernel<int64_t>, dim3((unsigned)num_samples), dim3(256), 0, stream,
-                           view_of<int64_t>(gr), a);
-    else
-        hipLaunchKernelGGL(unique_kernel<int32_t>, dim3((unsigned)num_samples), dim3(256), 0, stream,
-                           view_of<int32_t>(gr), a);
+#define ND_UNIQUE_LAUNCH(THREADS, PER)                                                              \
+    do {                                                                                            \
+        if (gr.off64)                                                                               \
+            hipLaunchKernelGGL((unique_kernel<int64_t, THREADS, PER>), dim3((unsigned)num_samples), \
+                               dim3(THREADS), 0, stream, view_of<int64_t>(gr), a);                  \
+        else                                                                                        \
+            hipLaunchKernelGGL((unique_kernel<int32_t, THREADS, PER>), dim3((unsigned)num_samples), \
+                               dim3(THREADS), 0, stream, view_of<int32_t>(gr), a);                  \
+    } while (0)
+    if (a.W <= 64) ND_UNIQUE_LAUNCH(64, 1);
+    else if (a.W <= 256) ND_UNIQUE_LAUNCH(256, 1);
+    else if (a.W <= 512) ND_UNIQUE_LAUNCH(256, 2);
+    else if (a.W <= 1024) ND_UNIQUE_LAUNCH(256, 4);
+    else ND_UNIQUE_LAUNCH(256, 8);
+#undef ND_UNIQUE_LAUNCH
     ND_HIP_CHECK(hipGetLastError());
     return ND_OK;
 }

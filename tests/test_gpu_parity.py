@@ -225,7 +225,8 @@ def test_khop_split_over_calls(small):
 # ----------------------------------------------------------------------------- unique neighbours
 @pytest.mark.parametrize("mode", [SP, TP])
 @pytest.mark.parametrize("fanout,rounds", [([25, 10], 4), ([6, 4], 1), ([3, 3, 3], 8), ([2048], 3),
-                                           ([40, 50], 2)])
+                                           ([40, 50], 2), ([20, 20], 3), ([30, 30], 2), ([64], 2),
+                                           ([65], 2), ([16, 16], 2), ([257], 2), ([1024], 2), ([1025], 2)])
 def test_khop_unique(small, mode, fanout, rounds):
     dg, og = device_graph(small)
     roots = np.arange(small.V, dtype=np.int32)[: 300 if max(np.cumprod(fanout)) > 1000 else small.V]
