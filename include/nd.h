@@ -279,6 +279,29 @@ int nd_layer_edges_fill(const nd_graph* g, const int32_t* transits_dev, int32_t 
 int nd_layer_edges_status(const void* workspace_dev, void* hip_stream);
 
 /*
+ * Output format 1 of Section 4.1 ("Output format": an array of samples, each
+ * holding all vertices sampled at all steps, as consumers of random walks and
+ * layer samples read them).  nd_sample writes format 2 (one array per step);
+ * this call gathers those arrays into one record per sample:
+ *
+ *   samples[s * record + off_i + j] = step_out[i][s * w_i + j]
+ *   w_i = step_len[i] / num_samples,  off_i = w_0 + ... + w_{i-1},  record = sum of w_i
+ *
+ *   step_out_dev   host array of num_steps device pointers (as given to nd_sample)
+ *   step_len       host array of num_steps lengths (as returned by nd_sample_query),
+ *                  each a positive multiple of num_samples
+ *   num_samples    walks and k-hop: the number of roots; layer and multi-
+ *                  dimensional walk: num_roots / roots_per_sample
+ *   samples_dev    device, num_samples * record int32
+ *
+ * A walk's record is its path without the root; a k-hop record lists hop 1,
+ * then hop 2, ...  Asynchronous on hip_stream; allocates nothing.  Errors:
+ * ND_ERR_NULL_POINTER, ND_ERR_BAD_ARGUMENT, ND_ERR_TOO_LARGE, ND_ERR_HIP.
+ */
+int nd_samples_pack(const int32_t* const* step_out_dev, int32_t num_steps, const int64_t* step_len,
+                    int64_t num_samples, int32_t* samples_dev, void* hip_stream);
+
+/*
  * Phase timing, for measurement.  After nd_profile_enable(1) on a thread, the
  * nd_sample calls of that thread bracket every phase of every step with HIP
  * events on their stream (a few microseconds per step; no synchronisation).

@@ -232,3 +232,11 @@ def layer_edges(g: OracleGraph, transits, sampled):
     _check(_load().ndo_layer_edges(g._h, t.ctypes.data, n_prev, v.ctypes.data, m, S, row_ptr.ctypes.data,
                                    edges.ctypes.data, edges.shape[0]), "layer_edges")
     return row_ptr, edges
+
+
+def pack_samples(steps):
+    """Output format 1 of Section 4.1: one record per sample holding what it gained at every
+    step, in step order.  `steps` is a list of [S, w_i] arrays (a walk's [L, S] array is a list of
+    L arrays of S entries); returns int32 [S, sum of w_i]."""
+    cols = [np.asarray(x, dtype=np.int32).reshape(len(x), -1) for x in steps]
+    return np.concatenate(cols, axis=1)

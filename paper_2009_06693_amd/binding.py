@@ -32,7 +32,7 @@ ND_ERR_NO_WEIGHTS, ND_ERR_WORKSPACE, ND_ERR_HIP, ND_ERR_BAD_ROOT, ND_ERR_TOO_LAR
 EXPORTS = ["nd_params_init", "nd_graph_create", "nd_graph_destroy", "nd_graph_info", "nd_sample_query",
            "nd_sample", "nd_sample_status", "nd_sample_stats", "nd_group_workspace_bytes",
            "nd_group_by_transit", "nd_layer_edges_workspace_bytes", "nd_layer_edges_count",
-           "nd_layer_edges_fill", "nd_layer_edges_status", "nd_profile_enable", "nd_profile_read", "nd_last_error", "nd_version"]
+           "nd_layer_edges_fill", "nd_layer_edges_status", "nd_samples_pack", "nd_profile_enable", "nd_profile_read", "nd_last_error", "nd_version"]
 
 ND_PHASES = ["init", "fill", "sort", "group", "sample_sub", "sample_wg", "sample_grid", "sample_sp",
              "layer", "unique"]
@@ -113,6 +113,8 @@ def lib() -> ctypes.CDLL:
         L.nd_layer_edges_fill.argtypes = [vp, vp, i32, vp, i32, i64, vp, vp, i64, vp]
         L.nd_layer_edges_status.restype = ctypes.c_int
         L.nd_layer_edges_status.argtypes = [vp, vp]
+        L.nd_samples_pack.restype = ctypes.c_int
+        L.nd_samples_pack.argtypes = [vp, i32, ctypes.POINTER(i64), i64, vp, vp]
         L.nd_profile_enable.restype = ctypes.c_int
         L.nd_profile_enable.argtypes = [ctypes.c_int]
         L.nd_profile_read.restype = ctypes.c_int
@@ -281,6 +283,26 @@ def nd_group_by_transit(transits: torch.Tensor, V: int, stream=None):
     c = counts.cpu()
     P, U = int(c[0]), int(c[1])
     return sk[:P], sv[:P], gk[:U], gs[:U + 1], P, U
+
+
+def nd_samples_pack(step_out: Sequence[torch.Tensor], num_samples: int, samples: Optional[torch.Tensor] = None,
+                    stream=None) -> torch.Tensor:
+    """Gathers the per-step arrays of an nd_sample call into one record per sample
+    (int32 [num_samples, record])."""
+    k = len(step_out)
+    for o in step_out:
+        if o.dtype != torch.int32 or not o.is_cuda or not o.is_contiguous():
+            raise TypeError("step arrays must be contiguous int32 CUDA tensors")
+    lens = (ctypes.c_int64 * k)(*[int(o.numel()) for o in step_out])
+    ptrs = (ctypes.c_void_p * k)(*[o.data_ptr() for o in step_out])
+    record = sum(int(o.numel()) // num_samples for o in step_out) if num_samples else 0
+    if samples is None:
+        samples = torch.empty((num_samples, record), dtype=torch.int32, device=step_out[0].device)
+    elif samples.dtype != torch.int32 or samples.numel() < num_samples * record or not samples.is_contiguous():
+        raise TypeError("samples must be a contiguous int32 tensor of num_samples * record entries")
+    _check(lib().nd_samples_pack(ptrs, k, lens, num_samples, samples.data_ptr() if samples.numel() else None,
+                                 _stream_ptr(stream)))
+    return samples
 
 
 def nd_layer_edges_workspace_bytes(num_samples: int, n_prev: int) -> int:

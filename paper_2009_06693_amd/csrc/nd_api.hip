@@ -11,6 +11,7 @@
 
 #include "nd_common.h"
 #include "nd_edges.h"
+#include "nd_pack.h"
 #include "nd_sample.h"
 
 struct nd_graph {
@@ -820,6 +821,42 @@ int nd_layer_edges_status(const void* workspace_dev, void* hip_stream) {
         return ND_ERR_BAD_ROOT;
     }
     return ND_OK;
+}
+
+int nd_samples_pack(const int32_t* const* step_out_dev, int32_t num_steps, const int64_t* step_len,
+                    int64_t num_samples, int32_t* samples_dev, void* hip_stream) {
+    if (num_steps < 1 || num_steps > ND_MAX_WALK_STEPS || num_samples < 0) {
+        set_error("num_steps must be in [1, %d] and num_samples not negative", ND_MAX_WALK_STEPS);
+        return ND_ERR_BAD_ARGUMENT;
+    }
+    if (!step_out_dev || !step_len || (num_samples > 0 && !samples_dev)) {
+        set_error("a required pointer is NULL");
+        return ND_ERR_NULL_POINTER;
+    }
+    int64_t record = 0;
+    for (int32_t i = 0; i < num_steps; ++i) {
+        if (step_len[i] < 0 || step_len[i] >= (1ll << 31)) {
+            set_error("step %d has %lld entries; at most 2^31 - 1", i, (long long)step_len[i]);
+            return ND_ERR_TOO_LARGE;
+        }
+        if (num_samples > 0) {
+            if (step_len[i] == 0 || step_len[i] % num_samples != 0) {
+                set_error("step %d: %lld entries is not a positive multiple of the %lld samples", i,
+                          (long long)step_len[i], (long long)num_samples);
+                return ND_ERR_BAD_ARGUMENT;
+            }
+            if (!step_out_dev[i]) {
+                set_error("a required pointer is NULL");
+                return ND_ERR_NULL_POINTER;
+            }
+            record += step_len[i] / num_samples;
+        }
+    }
+    if (record >= (1ll << 31)) {
+        set_error("a record of %lld entries is too long", (long long)record);
+        return ND_ERR_TOO_LARGE;
+    }
+    return pack_samples(step_out_dev, num_steps, step_len, num_samples, samples_dev, (hipStream_t)hip_stream);
 }
 
 }  // extern "C"
