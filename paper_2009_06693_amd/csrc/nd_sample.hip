@@ -193,21 +193,45 @@ struct PairCtx {
 
 // Branch-free on purpose: every load is issued unconditionally (from a clamped, always valid
 // index), so the loads of the U pairs a lane handles per round are in flight together.
+// Loading a pair is two dependent steps - the sorted pair itself, then the row offsets of its
+// transit - which the pipelined loop issues in different rounds.
+struct PairKey {
+    int32_t v;      // transit
+    uint32_t q;     // slot of the pair in the previous step's array
+    bool in_range;  // the pair exists
+};
+
+__device__ __forceinline__ PairKey load_pair_key(const int32_t* __restrict__ keys,
+                                                 const int32_t* __restrict__ vals, uint32_t pi,
+                                                 uint32_t P) {
+    PairKey k;
+    const uint32_t pc = pi < P ? pi : P - 1u;  // P >= 1 whenever a lane gets here
+    k.v = keys[pc];
+    k.q = (uint32_t)vals[pc];
+    k.in_range = pi < P;
+    return k;
+}
+
+template <bool HEAVY, typename OffT>
+__device__ __forceinline__ PairCtx load_pair_row(const GraphView<OffT>& g, const uint32_t* heavy_bits,
+                                                 const PairKey& k) {
+    PairCtx c;
+    c.v = k.v;
+    c.q = k.q;
+    uint32_t heavy = 0;
+    if (HEAVY) heavy = (heavy_bits[(uint32_t)c.v >> 5] >> ((uint32_t)c.v & 31u)) & 1u;
+    c.rs = (uint64_t)g.off[c.v];
+    c.deg = (uint32_t)((uint64_t)g.off[c.v + 1] - c.rs);
+    c.mine = k.in_range && heavy == 0u;
+    return c;
+}
+
 template <bool HEAVY, typename OffT>
 __device__ __forceinline__ PairCtx load_pair(const GraphView<OffT>& g,
                                              const int32_t* __restrict__ keys,
                                              const int32_t* __restrict__ vals,
                                              const uint32_t* heavy_bits, uint32_t pi, uint32_t P) {
-    PairCtx c;
-    const uint32_t pc = pi < P ? pi : P - 1u;  // P >= 1 whenever a lane gets here
-    c.v = keys[pc];
-    c.q = (uint32_t)vals[pc];
-    uint32_t heavy = 0;
-    if (HEAVY) heavy = (heavy_bits[(uint32_t)c.v >> 5] >> ((uint32_t)c.v & 31u)) & 1u;
-    c.rs = (uint64_t)g.off[c.v];
-    c.deg = (uint32_t)((uint64_t)g.off[c.v + 1] - c.rs);
-    c.mine = pi < P && heavy == 0u;
-    return c;
+    return load_pair_row<HEAVY>(g, heavy_bits, load_pair_key(keys, vals, pi, P));
 }
 
 template <int DRAW, typename OffT>
@@ -251,26 +275,34 @@ __device__ __forceinline__ void sub_loop(const GraphView<OffT>& g, const DrawArg
         const uint32_t stride = gridDim.x * pairs_per_block * U;
         uint32_t pi = blockIdx.x * pairs_per_block * U + pl;
         if (pi >= P) return;
-        // Software pipeline: the pair data of the next round is requested before this round's
-        // draws, and this round's stores are issued last, so neither the stores' acknowledgements
-        // nor the next loads are waited for while the generator runs.
+        // Software pipeline, three rounds deep: the sorted pairs of round i + 2 and the row offsets
+        // of round i + 1 are requested before round i draws, and round i's stores are issued last,
+        // so a lane never waits for two dependent loads in one round and neither the stores'
+        // acknowledgements nor the next loads are waited for while the generator runs.
         PairCtx cur[U];
+        PairKey key1[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u)
+        for (int u = 0; u < U; ++u) {
             cur[u] = load_pair<HEAVY>(g, keys, vals, heavy_bits, pi + u * pairs_per_block, P);
+            key1[u] = load_pair_key(keys, vals, pi + stride + u * pairs_per_block, P);
+        }
         for (; pi < P; pi += stride) {
+            PairKey key2[U];
             PairCtx nxt[U];
             int32_t res[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u)
-                nxt[u] = load_pair<HEAVY>(g, keys, vals, heavy_bits,
-                                          pi + stride + u * pairs_per_block, P);
+            for (int u = 0; u < U; ++u) {
+                // pi + 2 * stride stays below 2^32: P < 2^31 and a stride is at most a few million
+                key2[u] = load_pair_key(keys, vals, pi + 2u * stride + u * pairs_per_block, P);
+                nxt[u] = load_pair_row<HEAVY>(g, heavy_bits, key1[u]);
+            }
 #pragma unroll
             for (int u = 0; u < U; ++u) res[u] = draw_pair<DRAW>(g, a, cur[u], jj);
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 if (cur[u].mine) a.out[cur[u].q * a.m + jj] = res[u];  // below 2^31 by the call's plan
                 cur[u] = nxt[u];
+                key1[u] = key2[u];
             }
         }
     } else {
