@@ -130,6 +130,8 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--sub-max", type=int, default=0)
     ap.add_argument("--wg-max", type=int, default=0)
+    ap.add_argument("--group-bits", type=int, default=0,
+                    help="0: exact transit grouping (default); b: group by the top b bits of the vertex id only")
     ap.add_argument("--force-class", type=int, default=-1,
                     help="ablation: -1 balanced (default), 0/1/2 every transit sub-wavefront/workgroup/grid")
     args = ap.parse_args()
@@ -179,7 +181,7 @@ def main():
         roots_np = np.arange(g.V, dtype=np.int32)
     roots = torch.as_tensor(roots_np, device="cuda:0")
     mode = B.ND_MODE_TRANSIT_PARALLEL if args.mode == "tp" else B.ND_MODE_SAMPLE_PARALLEL
-    p = B.nd_params_init(mode=mode, sched_sub_max=args.sub_max, sched_wg_max=args.wg_max,
+    p = B.nd_params_init(mode=mode, sched_sub_max=args.sub_max, sched_wg_max=args.wg_max, sched_group_bits=args.group_bits,
                          sched_force_class=args.force_class, **pkw)
     s = B.Sampler(dg, app, p, int(roots.numel()))
     seed = 1
@@ -332,6 +334,7 @@ def main():
         "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "int32", "data": "synthetic",
         "config": {"workload": args.workload, "description": desc, "mode": args.mode,
+                   "group_bits": args.group_bits,
                    "graph": g.describe(), "roots": int(roots.numel()), "seed": seed,
                    "slots_per_step": slots, "non_null_per_step": live},
         "slots_per_s": round(slots / (ms_per_step * 1e-3), 1),

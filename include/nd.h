@@ -121,7 +121,13 @@ typedef struct nd_params {
                                /* held by a lower slot draws again (attempt 1 .. r-1) and is */
                                /* NULL if it never finds a free one.  Needs at most 2,048    */
                                /* slots per sample and step.                                 */
-    int32_t reserved[4];
+    int32_t sched_group_bits;  /* 0: group by the exact transit (the paper's scheduling   */
+                               /* index, three classes).  b > 0: group only by the top b  */
+                               /* bits of the transit's id - fewer radix passes, no       */
+                               /* segment scan or classification; every draw then goes    */
+                               /* through the lane-per-draw kernel, which needs transits  */
+                               /* to be near each other, not equal.  Same output.         */
+    int32_t reserved[3];
 } nd_params;
 
 typedef struct nd_graph nd_graph; /* opaque; owned by the library */

@@ -57,7 +57,8 @@ class nd_params(ctypes.Structure):
         ("sched_wg_max", ctypes.c_int32),
         ("lds_stage_policy", ctypes.c_int32),
         ("unique_rounds", ctypes.c_int32),
-        ("reserved", ctypes.c_int32 * 4),
+        ("sched_group_bits", ctypes.c_int32),
+        ("reserved", ctypes.c_int32 * 3),
     ]
 
 

@@ -96,7 +96,9 @@ int check_params(const Graph& g, int app, const nd_params* p, int64_t num_roots,
     }
     if (p->sched_force_class < ND_CLASS_AUTO || p->sched_force_class > ND_CLASS_GRID ||
         p->sched_sub_max < 0 || p->sched_wg_max < 0 || p->lds_stage_policy < 0 ||
-        p->lds_stage_policy > 2) {
+        p->lds_stage_policy > 2 || p->sched_group_bits < 0 || p->sched_group_bits > 31 ||
+        (p->sched_group_bits > 0 && p->sched_force_class != ND_CLASS_AUTO &&
+         p->sched_force_class != ND_CLASS_SUBWAVE)) {
         set_error("bad scheduling override");
         return ND_ERR_BAD_ARGUMENT;
     }
@@ -195,7 +197,7 @@ int check_params(const Graph& g, int app, const nd_params* p, int64_t num_roots,
                       ND_MAX_UNIQUE_SLOTS, i, (long long)(no / pl->S));
             return ND_ERR_BAD_ARGUMENT;
         }
-        const size_t hb = sort_hist_bytes(make_sort_plan(ns, g.V));
+        const size_t hb = sort_hist_bytes(make_sort_plan(ns, g.V, p->sched_group_bits));
         if (hb > pl->hist_bytes) pl->hist_bytes = hb;
     }
     return ND_OK;
@@ -581,7 +583,9 @@ int nd_sample(const nd_graph* h, int app, const nd_params* params, const int32_t
             continue;
         }
         SchedParams sp{m, pl.sub_max, pl.wg_max, params->sched_force_class};
-        const SortPlan plan = make_sort_plan(n_slots, g.V);
+        const bool coarse = params->sched_group_bits > 0;  // grouped by id prefix: no groups, one class
+        if (coarse) sp.force_class = ND_CLASS_SUBWAVE;
+        const SortPlan plan = make_sort_plan(n_slots, g.V, params->sched_group_bits);
         int32_t *keys = nullptr, *vals = nullptr;
         mark_phase(ND_PHASE_SORT, stream);
         rc = sort_pairs(src, n_slots, (int32_t)g.V, plan, (int32_t*)(ws + pl.o_keysA),
@@ -592,16 +596,18 @@ int nd_sample(const nd_graph* h, int app, const nd_params* params, const int32_t
         if (rc != ND_OK) return rc;
         int32_t* g_key = (int32_t*)(ws + pl.o_gkey);
         int32_t* g_start = (int32_t*)(ws + pl.o_gstart);
-        mark_phase(ND_PHASE_GROUP, stream);
-        rc = build_groups(keys, n_slots, ctl + i, g_key, g_start, (uint32_t*)(ws + pl.o_tiles), stream);
-        if (rc != ND_OK) return rc;
         int32_t* list_wg = (int32_t*)(ws + pl.o_list_wg);
         int32_t* chunk_gid = (int32_t*)(ws + pl.o_chunk_gid);
         int32_t* chunk_idx = (int32_t*)(ws + pl.o_chunk_idx);
         uint32_t* heavy_bits = sp.force_class == ND_CLASS_AUTO ? (uint32_t*)(ws + pl.o_bits) : nullptr;
-        rc = classify_groups(g_key, g_start, n_slots, ctl + i, sp, list_wg, chunk_gid, chunk_idx,
-                             pl.cap_chunks, heavy_bits, stream);
-        if (rc != ND_OK) return rc;
+        if (!coarse) {
+            mark_phase(ND_PHASE_GROUP, stream);
+            rc = build_groups(keys, n_slots, ctl + i, g_key, g_start, (uint32_t*)(ws + pl.o_tiles), stream);
+            if (rc != ND_OK) return rc;
+            rc = classify_groups(g_key, g_start, n_slots, ctl + i, sp, list_wg, chunk_gid, chunk_idx,
+                                 pl.cap_chunks, heavy_bits, stream);
+            if (rc != ND_OK) return rc;
+        }
         // work-list bounds for this step's launch shapes
         int64_t max_wg = n_out / pl.sub_max + 1;
         int64_t max_chunks = 2 * (n_out / pl.wg_max) + 1;

@@ -124,7 +124,8 @@ struct SortPlan {
     int tile;               // keys per tile
     int64_t max_tiles;      // tiles of the slot array (pass 0); later passes never need more
 };
-SortPlan make_sort_plan(int64_t n_slots, int64_t V);
+// group_bits > 0: sort on the top group_bits bits of the key only.
+SortPlan make_sort_plan(int64_t n_slots, int64_t V, int group_bits = 0);
 size_t sort_hist_bytes(const SortPlan& p);
 
 // Pass 0 reads `src` (n_slots transits, negative = no transit, implicit value = index)

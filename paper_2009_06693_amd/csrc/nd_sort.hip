@@ -20,12 +20,16 @@
 
 namespace nd {
 
-SortPlan make_sort_plan(int64_t n_slots, int64_t V) {
+SortPlan make_sort_plan(int64_t n_slots, int64_t V, int group_bits) {
     SortPlan p{};
     int nbits = 1;
     while ((1ll << nbits) < V) ++nbits;
-    p.passes = (nbits + kMaxRadixBits - 1) / kMaxRadixBits;
     int shift = 0;
+    if (group_bits > 0 && group_bits < nbits) {  // the low bits of the key are left unsorted
+        shift = nbits - group_bits;
+        nbits = group_bits;
+    }
+    p.passes = (nbits + kMaxRadixBits - 1) / kMaxRadixBits;
     for (int i = 0; i < p.passes; ++i) {
         p.bits[i] = nbits / p.passes + (i < nbits % p.passes ? 1 : 0);
         p.shift[i] = shift;

@@ -170,7 +170,12 @@ def test_config5_khop_and_deepwalk():
     _khop_properties(g, roots_t, out, [25, 10])
     stats = s.stats()
     assert stats[0, 0] == g.V and stats[1, 0] == int((out[0] >= 0).sum())
-    del s, out
+    # grouping by the top 8 bits of the transit id only (one radix pass, lane-per-draw kernel for
+    # every pair): another order of work, the same output
+    s2, out2 = _run(dg, B.ND_KHOP, roots, 5, num_steps=2, fanout=[25, 10], sched_group_bits=8)
+    _check_khop_windows(g, og, out2, [25, 10], 5, _windows(g.V, 512, 3, 59))
+    assert torch.equal(out2[0], out[0]) and torch.equal(out2[1], out[1])
+    del s, out, s2, out2
     torch.cuda.empty_cache()
     s, out = _run(dg, B.ND_DEEPWALK, roots, 5, num_steps=100)
     for a, b in _windows(g.V, 2048, 4, 56):
@@ -183,6 +188,8 @@ def test_config5_khop_and_deepwalk():
         nxt = out[i] >= 0
         assert bool((nxt <= alive).all())
         alive = nxt
+    s2, out2 = _run(dg, B.ND_DEEPWALK, roots, 5, num_steps=100, sched_group_bits=6)
+    assert all(torch.equal(a, b) for a, b in zip(out, out2))
 
 
 def test_unique_khop_on_the_large_graph():

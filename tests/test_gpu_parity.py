@@ -406,3 +406,36 @@ def test_argument_errors(small):
     with pytest.raises(B.NdError) as e:
         B.nd_sample(dg, B.ND_DEEPWALK, p, r, 1, s.out, s.workspace[:256])
     assert e.value.code == B.ND_ERR_WORKSPACE
+
+
+# ----------------------------------------------------------------------------- grouping by id prefix
+@pytest.mark.parametrize("bits", [1, 3, 8, 9, 31])
+def test_grouping_by_a_prefix_of_the_transit_id_gives_the_same_output(small, small_w, bits):
+    """sched_group_bits sorts the pairs on the top bits of the transit only; what is drawn does
+    not depend on the order in which pairs are processed."""
+    dg, og = device_graph(small)
+    roots = _roots(small, 7000, 21)
+    want = oracle.khop(og, roots, [7, 5], seed=61)
+    got, _ = gpu_sample(dg, B.ND_KHOP, roots, 61, num_steps=2, fanout=[7, 5], sched_group_bits=bits)
+    assert_steps_equal(got, [w.reshape(-1) for w in want], f"k-hop, {bits} group bits")
+    want = oracle.deepwalk(og, roots, 9, seed=62)
+    got, _ = gpu_sample(dg, B.ND_DEEPWALK, roots, 62, num_steps=9, sched_group_bits=bits)
+    assert_steps_equal(got, list(want), f"deepwalk, {bits} group bits")
+    dgw, ogw = device_graph(small_w)
+    roots = _roots(small_w, 5000, 22)
+    want = oracle.node2vec(ogw, roots, 6, 2.0, 0.5, seed=63, use_weights=True)
+    got, _ = gpu_sample(dgw, B.ND_NODE2VEC, roots, 63, num_steps=6, p=2.0, q=0.5, use_weights=1,
+                        sched_group_bits=bits)
+    assert_steps_equal(got, list(want), f"node2vec, {bits} group bits")
+    want = oracle.ppr(ogw, roots, 10, 0.05, seed=64, use_weights=True)
+    got, _ = gpu_sample(dgw, B.ND_PPR, roots, 64, num_steps=10, term_prob=0.05, use_weights=1,
+                        sched_group_bits=bits)
+    assert_steps_equal(got, list(want), f"ppr, {bits} group bits")
+
+
+def test_group_bits_with_a_forced_heavy_class_is_refused(small):
+    dg, _ = device_graph(small)
+    p = B.nd_params_init(num_steps=2, sched_group_bits=4, sched_force_class=B.ND_CLASS_WORKGROUP)
+    with pytest.raises(B.NdError) as e:
+        B.nd_sample_query(dg, B.ND_DEEPWALK, p, 10)
+    assert e.value.code == B.ND_ERR_BAD_ARGUMENT
