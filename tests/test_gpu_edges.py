@@ -97,3 +97,15 @@ def test_empty_and_error_cases():
     torch.cuda.synchronize()
     half = full.numel() // 2
     assert torch.equal(short[:half], full[:half]) and bool((short[half:] == -7).all())
+
+
+def test_edges_among_the_vertices_of_one_step():
+    """Cluster-style use (Section 4.2, "Cluster Sampling": an edge is recorded when it joins two
+    transits of the same step): the same array on both sides."""
+    g = _small
+    rng = np.random.default_rng(77)
+    hubs = np.argsort(-np.diff(g.row_offsets))[:400].astype(np.int32)
+    members = hubs[rng.integers(0, hubs.size, (6, 300))]
+    members[rng.random(members.shape) < 0.03] = -1
+    ptr = _compare(g, members, members)
+    assert ptr[-1] > 0
