@@ -44,6 +44,8 @@ WORKLOADS = {
                     "DeepWalk length 100, one walk per vertex, R-MAT scale 22"),
     "c3_khop": ("config3_graph", "khop", dict(num_steps=2, fanout=[25, 10]),
                 "k-hop [25,10], every vertex a root (228 batches of 1,024 in one call), 233K dense"),
+    "c4_khop": ("config4_graph", "khop", dict(num_steps=2, fanout=[25, 10]),
+                "k-hop [25,10], every vertex a root, 3M power-law (468 MB of adjacency: beyond the last-level cache)"),
     "c2_node2vec": ("config2_graph", "node2vec", dict(num_steps=100, p=2.0, q=0.5, use_weights=1),
                     "node2vec p=2 q=0.5 length 100, 57K power-law, weights U[1,5)"),
     "c2_ppr": ("config2_graph", "ppr", dict(num_steps=100, term_prob=0.01, use_weights=1),
