@@ -200,6 +200,11 @@ int nd_sample_query(const nd_graph* g, int app, const nd_params* params, int64_t
  *                    owned by the caller, reusable by the next call on the same
  *                    stream
  *
+ * The call only launches kernels (no allocation, no memset or copy, no wait
+ * for the device, no read-back), so it can be recorded into a HIP graph with
+ * stream capture and replayed; calls that use different workspaces and output
+ * arrays may run at the same time on different streams.
+ *
  * Errors (checked before anything is launched): ND_ERR_NULL_POINTER,
  * ND_ERR_BAD_ARGUMENT, ND_ERR_NO_WEIGHTS, ND_ERR_WORKSPACE, ND_ERR_TOO_LARGE,
  * ND_ERR_HIP.
