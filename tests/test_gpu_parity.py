@@ -431,6 +431,14 @@ def test_grouping_by_a_prefix_of_the_transit_id_gives_the_same_output(small, sma
     got, _ = gpu_sample(dgw, B.ND_PPR, roots, 64, num_steps=10, term_prob=0.05, use_weights=1,
                         sched_group_bits=bits)
     assert_steps_equal(got, list(want), f"ppr, {bits} group bits")
+    want = oracle.khop(og, roots[:2000], [12, 6], seed=65, unique_rounds=3)
+    got, _ = gpu_sample(dg, B.ND_KHOP, roots[:2000], 65, num_steps=2, fanout=[12, 6], unique_rounds=3,
+                        sched_group_bits=bits)
+    assert_steps_equal(got, [w.reshape(-1) for w in want], f"unique k-hop, {bits} group bits")
+    want = oracle.multirw(og, roots[:4000], 8, 12, seed=66)
+    got, _ = gpu_sample(dg, B.ND_MULTIRW, roots[:4000], 66, num_steps=12, roots_per_sample=8,
+                        sched_group_bits=bits)
+    assert_steps_equal(got, list(want), f"multi-dimensional walk, {bits} group bits")
 
 
 def test_group_bits_with_a_forced_heavy_class_is_refused(small):
