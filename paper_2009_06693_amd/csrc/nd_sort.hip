@@ -127,17 +127,18 @@ __global__ __launch_bounds__(THREADS) void upsweep_kernel(
 
 // One workgroup per digit value: exclusive scan of that digit's per-tile counts,
 // in place; the digit's total goes to bin_total[digit].
-__global__ __launch_bounds__(256) void binscan_kernel(uint32_t* __restrict__ hist,
-                                                      uint32_t* __restrict__ bin_total,
-                                                      int64_t num_tiles) {
-    __shared__ uint32_t tmp[8];
+constexpr int kBinscanThreads = 1024;
+__global__ __launch_bounds__(kBinscanThreads) void binscan_kernel(uint32_t* __restrict__ hist,
+                                                                  uint32_t* __restrict__ bin_total,
+                                                                  int64_t num_tiles) {
+    __shared__ uint32_t tmp[kBinscanThreads / 64 + 1];
     uint32_t* row = hist + (int64_t)blockIdx.x * num_tiles;
     uint32_t carry = 0;
-    for (int64_t base = 0; base < num_tiles; base += 256) {
+    for (int64_t base = 0; base < num_tiles; base += kBinscanThreads) {
         const int64_t i = base + threadIdx.x;
         const uint32_t x = i < num_tiles ? row[i] : 0u;
         uint32_t total;
-        const uint32_t ex = block_exclusive_scan<uint32_t, 256>(x, tmp, &total);
+        const uint32_t ex = block_exclusive_scan<uint32_t, kBinscanThreads>(x, tmp, &total);
         if (i < num_tiles) row[i] = carry + ex;
         carry += total;
         __syncthreads();
@@ -294,7 +295,7 @@ int sort_pairs_impl(const int32_t* src, int64_t n_slots, int32_t V, const SortPl
                                dim3(THREADS), 0, stream, kin, n_slots, ctl, shift, bits, hist, tiles, V,
                                0, (uint32_t*)nullptr, (int32_t*)nullptr, make_fastdiv(1u), 0);
         }
-        hipLaunchKernelGGL(binscan_kernel, dim3(1u << bits), dim3(256), 0, stream, hist, bin_total,
+        hipLaunchKernelGGL(binscan_kernel, dim3(1u << bits), dim3(kBinscanThreads), 0, stream, hist, bin_total,
                            tiles);
         if (p == 0) {
             hipLaunchKernelGGL((downsweep_kernel<true, THREADS, ITEMS>), dim3((unsigned)tiles),
