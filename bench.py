@@ -221,7 +221,7 @@ def main():
     stats = s.stats() if (mode == B.ND_MODE_TRANSIT_PARALLEL and app != B.ND_LAYER) else None
     phase_ms = {k: v[0] / args.steps for k, v in phases.items() if v[1] > 0}
     launches = {k: v[1] / args.steps for k, v in phases.items() if v[1] > 0}
-    kernel_phases = [k for k in ("sample_sub", "sample_sp", "layer", "sample_wg", "sample_grid") if k in phase_ms]
+    kernel_phases = [k for k in ("sample_sub", "sample_sp", "layer", "sample_wg") if k in phase_ms]
     dom = max(kernel_phases, key=lambda k: phase_ms[k])
     avg_launch_ms = phase_ms[dom] / launches[dom]
     if stats is not None and dom == "sample_sub":
@@ -257,8 +257,7 @@ def main():
     draws_per_s = draws_per_launch / (avg_launch_ms * 1e-3)
     roofline = {
         "kernel": {"sample_sub": "sample_sub_kernel", "sample_sp": "sample_sp_kernel",
-                   "layer": "layer_kernel", "sample_wg": "sample_wg_kernel<.., false>",
-                   "sample_grid": "sample_wg_kernel<.., true>"}[dom],
+                   "layer": "layer_kernel", "sample_wg": "sample_wg_kernel"}[dom],
         "bound": "hbm", "achieved": round(hbm_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(hbm_gbs / HBM_PEAK_GBS, 4),
         "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, args.mode, dom)),

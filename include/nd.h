@@ -327,16 +327,14 @@ int nd_samples_pack(const int32_t* const* step_out_dev, int32_t num_steps, const
 typedef enum nd_phase {
     ND_PHASE_NONE = -1,
     ND_PHASE_INIT = 0,        /* workspace header / bitmap reset                    */
-    ND_PHASE_FILL = 1,        /* unused (the NULL fill is part of the sort's pass 0) */
-    ND_PHASE_SORT = 2,        /* transit enumeration + radix sort by transit        */
-    ND_PHASE_GROUP = 3,       /* segmented scan + classification                    */
-    ND_PHASE_SAMPLE_SUB = 4,  /* sub-wavefront class kernel                         */
-    ND_PHASE_SAMPLE_WG = 5,   /* workgroup and grid class kernel (one launch)       */
-    ND_PHASE_SAMPLE_GRID = 6, /* unused                                             */
-    ND_PHASE_SAMPLE_SP = 7,   /* sample-parallel kernel (ablation mode)             */
-    ND_PHASE_LAYER = 8,       /* collective (layer) kernel                          */
-    ND_PHASE_UNIQUE = 9,      /* duplicate removal and refill (unique neighbours)   */
-    ND_PHASE_COUNT = 10
+    ND_PHASE_SORT = 1,        /* transit enumeration, NULL fill + radix sort        */
+    ND_PHASE_GROUP = 2,       /* segmented scan + classification                    */
+    ND_PHASE_SAMPLE_SUB = 3,  /* sub-wavefront class kernel                         */
+    ND_PHASE_SAMPLE_WG = 4,   /* workgroup and grid class kernel (one launch)       */
+    ND_PHASE_SAMPLE_SP = 5,   /* sample-parallel kernel (ablation mode)             */
+    ND_PHASE_LAYER = 6,       /* collective (layer) kernel                          */
+    ND_PHASE_UNIQUE = 7,      /* duplicate removal and refill (unique neighbours)   */
+    ND_PHASE_COUNT = 8
 } nd_phase;
 int nd_profile_enable(int on);
 int nd_profile_read(double* ms, int64_t* intervals);

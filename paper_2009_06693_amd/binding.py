@@ -34,8 +34,7 @@ EXPORTS = ["nd_params_init", "nd_graph_create", "nd_graph_destroy", "nd_graph_in
            "nd_group_by_transit", "nd_layer_edges_workspace_bytes", "nd_layer_edges_count",
            "nd_layer_edges_fill", "nd_layer_edges_status", "nd_samples_pack", "nd_profile_enable", "nd_profile_read", "nd_last_error", "nd_version"]
 
-ND_PHASES = ["init", "fill", "sort", "group", "sample_sub", "sample_wg", "sample_grid", "sample_sp",
-             "layer", "unique"]
+ND_PHASES = ["init", "sort", "group", "sample_sub", "sample_wg", "sample_sp", "layer", "unique"]
 
 
 class nd_params(ctypes.Structure):

@@ -93,10 +93,10 @@ struct StepCtl {
     uint32_t n_wg;          // transits in the workgroup class
     uint32_t n_grid;        // transits in the grid class
     uint32_t n_chunks;      // grid chunks
-    uint32_t n_sub;         // unused on the device (U - n_wg - n_grid)
+    uint32_t reserved0;
     uint32_t n_staged;      // workgroup/grid work items that staged their list in LDS
     uint32_t wg_cursor;     // next workgroup-class item to hand out
-    uint32_t grid_cursor;   // next grid chunk to hand out
+    uint32_t reserved1;
     uint32_t heavy_draws;   // draws of the workgroup- and grid-class transits
     uint32_t pad[6];
 };

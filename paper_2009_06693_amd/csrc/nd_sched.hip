@@ -75,11 +75,9 @@ __global__ __launch_bounds__(1024) void seg_scan_kernel(uint32_t* __restrict__ t
         ctl->n_wg = 0;
         ctl->n_grid = 0;
         ctl->n_chunks = 0;
-        ctl->n_sub = 0;
         ctl->heavy_draws = 0;
         ctl->n_staged = 0;
         ctl->wg_cursor = 0;
-        ctl->grid_cursor = 0;
         g_start[carry] = (int32_t)ctl->P;  // sentinel: end of the last group
     }
 }
