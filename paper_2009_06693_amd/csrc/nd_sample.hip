@@ -1,25 +1,29 @@
 // Sampling kernels for individual transit sampling (random walks and k-hop;
 // Section 6.1 of the paper).
 //
-// Three transit-parallel kernels, one per scheduling class of Section 6.1.2
-// (Table "Types of kernels"), re-derived for 64-lane wavefronts:
-//   sub-wavefront  64 consecutive transits share a wavefront; every draw gets a
-//                  lane, the draws of one (transit, sample) pair sit on
-//                  consecutive lanes so the sample's new vertices leave in one
-//                  contiguous store (the paper's sub-warps, Section 6.1.1);
-//                  per-transit data is fetched once per transit and handed to
-//                  the drawing lanes through LDS.
-//   workgroup      one 256-lane workgroup per transit; the adjacency list (and
-//                  the weight running sums) are staged in LDS when they fit and
-//                  the reuse pays for the copy, otherwise read from global
-//                  memory ("Caching", Section 6.1.2).
+// The three scheduling classes of Section 6.1.2 (Table "Types of kernels"),
+// re-derived for 64-lane wavefronts and run as two launches per step:
+//   sub-wavefront  one lane per draw over the pairs sorted by transit; the
+//                  draws of one (transit, sample) pair sit on consecutive lanes,
+//                  so the sample's new vertices leave in one contiguous store
+//                  (the paper's sub-warps, Section 6.1.1), and neighbouring
+//                  lanes read the same or neighbouring adjacency lists, which
+//                  the caches serve once.  No LDS; three-round software pipeline.
+//   workgroup      one 1,024-lane workgroup at a time per transit, handed out
+//                  by a device-side cursor; the adjacency list (and the weight
+//                  running sums) are staged in LDS when they fit and the reuse
+//                  pays for the copy, otherwise read from global memory
+//                  ("Caching", Section 6.1.2).
 //   grid           a transit with more draws than one workgroup handles is cut
-//                  into chunks, one workgroup each, every chunk staging the list.
+//                  into chunks that go through the same kernel and cursor as the
+//                  workgroup class, every chunk staging the list.
 // plus the sample-parallel kernel of Section 5.1 (one lane per output slot, no
-// grouping), kept as the ablation baseline.
+// grouping), kept as the ablation baseline, the per-sample kernel that removes
+// repeated neighbours (Section 6.3) and the small kernels of the
+// multi-dimensional walk.
 //
-// What a lane draws is the same in all four: one Philox call per
-// (sample, slot, step, attempt), so the four produce identical outputs.
+// What a lane draws is the same in all of them: one Philox call per
+// (sample, slot, step, attempt), so they produce identical outputs.
 #include "nd_common.h"
 #include "nd_philox.h"
 #include "nd_wave.h"
