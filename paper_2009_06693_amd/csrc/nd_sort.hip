@@ -31,7 +31,9 @@ SortPlan make_sort_plan(int64_t n_slots, int64_t V, int group_bits) {
     }
     p.passes = (nbits + kMaxRadixBits - 1) / kMaxRadixBits;
     for (int i = 0; i < p.passes; ++i) {
-        p.bits[i] = nbits / p.passes + (i < nbits % p.passes ? 1 : 0);
+        // the wider digits go last: pass 0 also carries the slots without a transit, so its tiles
+        // hold fewer live pairs and fewer bins keep its scattered runs longer
+        p.bits[i] = nbits / p.passes + (i >= p.passes - nbits % p.passes ? 1 : 0);
         p.shift[i] = shift;
         shift += p.bits[i];
     }
@@ -200,13 +202,48 @@ __global__ __launch_bounds__(THREADS) void downsweep_kernel(
         key[r] = k;
         val[r] = v;
     }
+    // Pass 0 sees the slots without a transit as well (nearly half of them in the k-hop
+    // workload on a graph with many isolated vertices).  The wave squeezes them out of its
+    // 1024 slots first, through its own part of the reorder buffer and keeping the order, so
+    // that the ranking below spends its ballots on live pairs only.
+    uint32_t wave_live = (uint32_t)kPerWave;
+    int32_t* stage_k = skeys + wave * kPerWave;
+    int32_t* stage_v = svals + wave * kPerWave;
+    if (FIRST) {
+        uint32_t cnt = 0;
+#pragma unroll
+        for (int r = 0; r < ITEMS; ++r) {
+            const bool live = key[r] >= 0;
+            const uint64_t bal = __ballot(live);
+            if (live) {
+                const uint32_t p = cnt + (uint32_t)__popcll(bal & lanes_below(lane));
+                stage_k[p] = key[r];
+                stage_v[p] = val[r];
+            }
+            cnt += (uint32_t)__popcll(bal);
+        }
+        wave_live = cnt;
+    }
     __syncthreads();
+    if (FIRST) {
+#pragma unroll
+        for (int r = 0; r < ITEMS; ++r) {
+            const uint32_t i = (uint32_t)(r * 64 + lane);
+            const bool live = i < wave_live;
+            key[r] = live ? stage_k[live ? i : 0u] : ND_NULL_VERTEX;
+            val[r] = live ? stage_v[live ? i : 0u] : 0;
+        }
+    }
 
     // Stable rank inside the wave's 1024 consecutive keys: for every group of 64
     // keys, the lanes holding the same digit are found with one ballot per digit
     // bit; the lowest such lane advances the wave's running count of the digit.
 #pragma unroll
     for (int r = 0; r < ITEMS; ++r) {
+        if ((uint32_t)(r * 64) >= wave_live) {  // the same for the whole wave: nothing left to rank
+            rank[r] = 0;
+            continue;
+        }
         const bool live = key[r] >= 0;
         const uint32_t d = ((uint32_t)key[r] >> shift) & mask;
         uint64_t peers = __ballot(live);
