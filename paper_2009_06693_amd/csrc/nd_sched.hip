@@ -12,7 +12,7 @@ namespace nd {
 
 size_t seg_scratch_bytes(int64_t n_slots) {
     const int64_t tiles = (n_slots + kSegTile - 1) / kSegTile + 1;
-    return (size_t)tiles * sizeof(uint32_t);
+    return (size_t)tiles * (kSegThreads / 64) * sizeof(uint32_t);  // one head count per wavefront
 }
 
 namespace {
@@ -30,31 +30,41 @@ __device__ __forceinline__ bool is_head(const int32_t* __restrict__ keys, int64_
     return idx < P && k != prev;
 }
 
+// Heads among the 1,024 consecutive pairs of every wavefront; a lane looks at four
+// consecutive keys per round (one 16-byte load) and compares them with each other, the first
+// with the last key of the lane before.
 __global__ __launch_bounds__(kSegThreads) void seg_count_kernel(const int32_t* __restrict__ keys,
                                                                 const StepCtl* __restrict__ ctl,
-                                                                uint32_t* __restrict__ tile_counts) {
-    __shared__ uint32_t wsum[kSegWaves];
+                                                                uint32_t* __restrict__ wave_counts) {
     const int lane = lane_id(), wave = wave_id();
     const int64_t P = ctl->P;
     const int64_t base = (int64_t)blockIdx.x * kSegTile + (int64_t)wave * kSegPerWave;
     uint32_t cnt = 0;
-    if ((int64_t)blockIdx.x * kSegTile < P) {
-        for (int r = 0; r < kSegPerWave / 64; ++r) {
-            int32_t k;
-            const bool h = is_head(keys, base + r * 64 + lane, P, lane, &k);
-            cnt += (uint32_t)__popcll(__ballot(h));
+    if (base < P) {
+#pragma unroll
+        for (int r = 0; r < kSegPerWave / 256; ++r) {
+            const int64_t idx = base + r * 256 + lane * 4;
+            int32_t k[4] = {-2, -2, -2, -2};
+            if (idx + 3 < P) {
+                const int4 v = *reinterpret_cast<const int4*>(keys + idx);  // idx is a multiple of 4
+                k[0] = v.x; k[1] = v.y; k[2] = v.z; k[3] = v.w;
+            } else {
+                for (int e = 0; e < 4; ++e)
+                    if (idx + e < P) k[e] = keys[idx + e];
+            }
+            int32_t prev = __shfl_up(k[3], 1, 64);
+            if (lane == 0) prev = (idx > 0 && idx < P) ? keys[idx - 1] : -3;
+            cnt += (idx < P && k[0] != prev) ? 1u : 0u;
+            cnt += (idx + 1 < P && k[1] != k[0]) ? 1u : 0u;
+            cnt += (idx + 2 < P && k[2] != k[1]) ? 1u : 0u;
+            cnt += (idx + 3 < P && k[3] != k[2]) ? 1u : 0u;
         }
     }
-    if (lane == 0) wsum[wave] = cnt;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t t = 0;
-        for (int w = 0; w < kSegWaves; ++w) t += wsum[w];
-        tile_counts[blockIdx.x] = t;
-    }
+    const uint32_t incl = wave_inclusive_scan(cnt, lane);
+    if (lane == 63) wave_counts[(int64_t)blockIdx.x * kSegWaves + wave] = incl;
 }
 
-// One workgroup: exclusive scan of the per-tile head counts in place, publishes
+// One workgroup: exclusive scan of the per-wavefront head counts in place, publishes
 // the number of groups and resets the class counters of the step.
 __global__ __launch_bounds__(1024) void seg_scan_kernel(uint32_t* __restrict__ tile_counts,
                                                         int64_t num_tiles, StepCtl* __restrict__ ctl,
@@ -87,23 +97,12 @@ __global__ __launch_bounds__(kSegThreads) void seg_write_kernel(const int32_t* _
                                                                 const uint32_t* __restrict__ tile_offs,
                                                                 int32_t* __restrict__ g_key,
                                                                 int32_t* __restrict__ g_start) {
-    __shared__ uint32_t wsum[kSegWaves];
     const int lane = lane_id(), wave = wave_id();
     const int64_t P = ctl->P;
-    if ((int64_t)blockIdx.x * kSegTile >= P) return;
     const int64_t base = (int64_t)blockIdx.x * kSegTile + (int64_t)wave * kSegPerWave;
-    // pass 1: heads per wave
-    uint32_t cnt = 0;
-    for (int r = 0; r < kSegPerWave / 64; ++r) {
-        int32_t k;
-        const bool h = is_head(keys, base + r * 64 + lane, P, lane, &k);
-        cnt += (uint32_t)__popcll(__ballot(h));
-    }
-    if (lane == 0) wsum[wave] = cnt;
-    __syncthreads();
-    uint32_t gid = tile_offs[blockIdx.x];
-    for (int w = 0; w < wave; ++w) gid += wsum[w];
-    // pass 2: group ids by ballot prefix (keys are in cache from pass 1)
+    if (base >= P) return;
+    uint32_t gid = tile_offs[(int64_t)blockIdx.x * kSegWaves + wave];  // groups that start before this wave
+    // group ids by ballot prefix
     for (int r = 0; r < kSegPerWave / 64; ++r) {
         int32_t k;
         const int64_t idx = base + r * 64 + lane;
@@ -217,8 +216,8 @@ int build_groups(const int32_t* sorted_keys, int64_t max_pairs, StepCtl* ctl, in
     if (tiles < 1) tiles = 1;
     hipLaunchKernelGGL(seg_count_kernel, dim3((unsigned)tiles), dim3(kSegThreads), 0, stream,
                        sorted_keys, ctl, tile_counts);
-    hipLaunchKernelGGL(seg_scan_kernel, dim3(1), dim3(1024), 0, stream, tile_counts, tiles, ctl,
-                       g_start);
+    hipLaunchKernelGGL(seg_scan_kernel, dim3(1), dim3(1024), 0, stream, tile_counts,
+                       tiles * (kSegThreads / 64), ctl, g_start);
     hipLaunchKernelGGL(seg_write_kernel, dim3((unsigned)tiles), dim3(kSegThreads), 0, stream,
                        sorted_keys, ctl, tile_counts, g_key, g_start);
     ND_HIP_CHECK(hipGetLastError());
