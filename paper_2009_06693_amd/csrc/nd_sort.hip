@@ -77,7 +77,24 @@ __global__ __launch_bounds__(THREADS) void upsweep_kernel(
     if (tid < nbins) h[tid] = 0;
     __syncthreads();
     bool bad = false;
-    if (base < n) {
+    if (!FIRST && base < n) {
+        // live pairs only: four consecutive keys per lane and load (the tile base is a multiple of 4)
+#pragma unroll 4
+        for (int i = tid * 4; i < kTile; i += THREADS * 4) {
+            const int64_t idx = base + i;
+            if (idx + 3 < n) {
+                const int4 v = *reinterpret_cast<const int4*>(keys + idx);
+                atomicAdd(&h[((uint32_t)v.x >> shift) & mask], 1u);
+                atomicAdd(&h[((uint32_t)v.y >> shift) & mask], 1u);
+                atomicAdd(&h[((uint32_t)v.z >> shift) & mask], 1u);
+                atomicAdd(&h[((uint32_t)v.w >> shift) & mask], 1u);
+            } else {
+                for (int e = 0; e < 4; ++e)
+                    if (idx + e < n) atomicAdd(&h[((uint32_t)keys[idx + e] >> shift) & mask], 1u);
+            }
+        }
+    }
+    if (FIRST && base < n) {
 #pragma unroll 4
         for (int i = tid; i < kTile; i += THREADS) {
             const int64_t idx = base + i;  // a wavefront covers 64 consecutive slots
