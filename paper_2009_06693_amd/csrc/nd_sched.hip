@@ -118,6 +118,56 @@ __global__ __launch_bounds__(kSegThreads) void seg_write_kernel(const int32_t* _
 }
 
 
+// Few pairs (a walk on a small graph): the three kernels above in one workgroup of 16
+// wavefronts, each taking a sixteenth of the pairs - heads per wavefront, their prefix over
+// the wavefronts, then the group table.  Saves two launches per step where a launch costs
+// more than the work.
+constexpr int64_t kSegSmallLimit = 8192;
+__global__ __launch_bounds__(1024) void seg_small_kernel(const int32_t* __restrict__ keys,
+                                                         StepCtl* __restrict__ ctl,
+                                                         int32_t* __restrict__ g_key,
+                                                         int32_t* __restrict__ g_start) {
+    __shared__ uint32_t wsum[16];
+    const int lane = lane_id(), wave = wave_id();
+    const int64_t P = ctl->P;
+    const int64_t per_wave = ((P + 15) / 16 + 63) / 64 * 64;
+    const int64_t wb = (int64_t)wave * per_wave;
+    const int64_t we = wb + per_wave < P ? wb + per_wave : P;
+    uint32_t cnt = 0;
+    for (int64_t i = wb; i < we; i += 64) {
+        int32_t k;
+        cnt += (uint32_t)__popcll(__ballot(is_head(keys, i + lane, P, lane, &k)));
+    }
+    if (lane == 0) wsum[wave] = cnt;
+    __syncthreads();
+    uint32_t gid = 0, total = 0;
+    for (int w = 0; w < 16; ++w) {
+        gid += w < wave ? wsum[w] : 0u;
+        total += wsum[w];
+    }
+    for (int64_t i = wb; i < we; i += 64) {
+        int32_t k;
+        const bool h = is_head(keys, i + lane, P, lane, &k);
+        const uint64_t bal = __ballot(h);
+        if (h) {
+            const uint32_t g = gid + (uint32_t)__popcll(bal & lanes_below(lane));
+            g_key[g] = k;
+            g_start[g] = (int32_t)(i + lane);
+        }
+        gid += (uint32_t)__popcll(bal);
+    }
+    if (threadIdx.x == 0) {
+        ctl->U = total;
+        ctl->n_wg = 0;
+        ctl->n_grid = 0;
+        ctl->n_chunks = 0;
+        ctl->heavy_draws = 0;
+        ctl->n_staged = 0;
+        ctl->wg_cursor = 0;
+        g_start[total] = (int32_t)P;  // sentinel: end of the last group
+    }
+}
+
 // One lane per transit, 1024 transits per workgroup round.  List space is
 // reserved with one atomic per class per round (counts are combined with wave64
 // ballots and a small LDS table first), so list order follows transit order
@@ -212,6 +262,11 @@ __global__ __launch_bounds__(256) void classify_kernel(const int32_t* __restrict
 
 int build_groups(const int32_t* sorted_keys, int64_t max_pairs, StepCtl* ctl, int32_t* g_key,
                  int32_t* g_start, uint32_t* tile_counts, hipStream_t stream) {
+    if (max_pairs <= kSegSmallLimit) {
+        hipLaunchKernelGGL(seg_small_kernel, dim3(1), dim3(1024), 0, stream, sorted_keys, ctl, g_key, g_start);
+        ND_HIP_CHECK(hipGetLastError());
+        return ND_OK;
+    }
     int64_t tiles = (max_pairs + kSegTile - 1) / kSegTile;
     if (tiles < 1) tiles = 1;
     hipLaunchKernelGGL(seg_count_kernel, dim3((unsigned)tiles), dim3(kSegThreads), 0, stream,

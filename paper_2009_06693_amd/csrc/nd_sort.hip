@@ -147,6 +147,7 @@ __global__ __launch_bounds__(THREADS) void upsweep_kernel(
 // One workgroup per digit value: exclusive scan of that digit's per-tile counts,
 // in place; the digit's total goes to bin_total[digit].
 constexpr int kBinscanThreads = 1024;
+constexpr int64_t kFusedScanTiles = 64;  // up to here the downsweep scans the tiles itself
 __global__ __launch_bounds__(kBinscanThreads) void binscan_kernel(uint32_t* __restrict__ hist,
                                                                   uint32_t* __restrict__ bin_total,
                                                                   int64_t num_tiles) {
@@ -190,11 +191,27 @@ __global__ __launch_bounds__(THREADS) void downsweep_kernel(
 
     // Global start of every digit = exclusive scan of the digit totals; the sum
     // of the totals is the number of live pairs, which pass 0 publishes.
+    // With few tiles the scan over the tiles is not a kernel of its own (bin_total is null):
+    // every workgroup adds up its digit's row of raw per-tile counts itself.
     {
-        const uint32_t t = tid < nbins ? bin_total[tid] : 0u;
+        uint32_t t = 0, before = 0;
+        if (tid < nbins) {
+            const uint32_t* row = hist + (int64_t)tid * num_tiles;
+            if (bin_total != nullptr) {
+                t = bin_total[tid];
+                before = row[blockIdx.x];
+            } else {
+#pragma unroll 8
+                for (int tt = 0; tt < (int)num_tiles; ++tt) {  // independent loads, at most 64
+                    const uint32_t c = row[tt];
+                    t += c;
+                    before += tt < (int)blockIdx.x ? c : 0u;
+                }
+            }
+        }
         uint32_t total;
         const uint32_t ex = block_exclusive_scan<uint32_t, THREADS>(t, scan_tmp, &total);
-        if (tid < nbins) global_base[tid] = ex + hist[(int64_t)tid * num_tiles + blockIdx.x];
+        if (tid < nbins) global_base[tid] = ex + before;
         if (FIRST && blockIdx.x == 0 && tid == 0) ctl->P = total;
     }
     if (base >= n) return;  // uniform for the workgroup
@@ -349,16 +366,20 @@ int sort_pairs_impl(const int32_t* src, int64_t n_slots, int32_t V, const SortPl
                                dim3(THREADS), 0, stream, kin, n_slots, ctl, shift, bits, hist, tiles, V,
                                0, (uint32_t*)nullptr, (int32_t*)nullptr, make_fastdiv(1u), 0);
         }
-        hipLaunchKernelGGL(binscan_kernel, dim3(1u << bits), dim3(kBinscanThreads), 0, stream, hist, bin_total,
-                           tiles);
+        // the launch of a scan kernel costs more than 64 loads per digit in every workgroup
+        const bool own_scan = tiles > kFusedScanTiles;
+        const uint32_t* totals = own_scan ? bin_total : nullptr;
+        if (own_scan)
+            hipLaunchKernelGGL(binscan_kernel, dim3(1u << bits), dim3(kBinscanThreads), 0, stream, hist,
+                               bin_total, tiles);
         if (p == 0) {
             hipLaunchKernelGGL((downsweep_kernel<true, THREADS, ITEMS>), dim3((unsigned)tiles),
                                dim3(THREADS), 0, stream, kin, vin, n_slots, ctl, shift, bits, hist,
-                               bin_total, tiles, kout, vout, V);
+                               totals, tiles, kout, vout, V);
         } else {
             hipLaunchKernelGGL((downsweep_kernel<false, THREADS, ITEMS>), dim3((unsigned)tiles),
                                dim3(THREADS), 0, stream, kin, vin, n_slots, ctl, shift, bits, hist,
-                               bin_total, tiles, kout, vout, V);
+                               totals, tiles, kout, vout, V);
         }
         kin = kout;
         vin = vout;
