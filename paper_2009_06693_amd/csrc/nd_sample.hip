@@ -490,7 +490,7 @@ int launch_sp(const Graph& gr, const DrawArgs& a, const int32_t* src, int64_t n_
 // so the outcome does not depend on the order in which lanes arrive.  Slots that lose draw
 // again straight from the graph (the paper's sample-parallel refill).
 // The workgroup is sized to the sample: THREADS * kPerThread >= W slots, one wavefront for the
-// 25-slot first hop of GraphSAGE, 256 threads for its 250-slot second hop.
+// 25-slot first hop of GraphSAGE and, four slots per lane, for its 250-slot second hop.
 template <typename OffT, int THREADS, int kPerThread>
 __global__ __launch_bounds__(THREADS) void unique_kernel(GraphView<OffT> g, UniqueArgs a) {
     constexpr uint32_t kBuckets = 2 * THREADS * kPerThread;
@@ -506,11 +506,13 @@ __global__ __launch_bounds__(THREADS) void unique_kernel(GraphView<OffT> g, Uniq
     // round 0 was drawn by the step's ordinary kernels: every vertex in the row is a candidate
     int32_t cand[kPerThread];               // candidate of my slot t (NULL: nothing to place)
     int32_t held[kPerThread];               // what my slot t ends up holding
+    int32_t first[kPerThread];              // what the step's ordinary kernels left there
     int any_candidate = 0;
 #pragma unroll
     for (int t = 0; t < kPerThread; ++t) {
         const uint32_t j = threadIdx.x + (uint32_t)t * (uint32_t)THREADS;
         cand[t] = j < W ? out_row[j] : ND_NULL_VERTEX;
+        first[t] = cand[t];
         held[t] = ND_NULL_VERTEX;
         any_candidate |= cand[t] >= 0 ? 1 : 0;
     }
@@ -577,7 +579,7 @@ __global__ __launch_bounds__(THREADS) void unique_kernel(GraphView<OffT> g, Uniq
 #pragma unroll
     for (int t = 0; t < kPerThread; ++t) {
         const uint32_t j = threadIdx.x + (uint32_t)t * (uint32_t)THREADS;
-        if (j < W) out_row[j] = held[t];
+        if (j < W && held[t] != first[t]) out_row[j] = held[t];  // most slots keep their first draw
     }
 }
 
@@ -626,8 +628,10 @@ int unique_step(const Graph& gr, const UniqueArgs& a, int64_t num_samples, hipSt
             hipLaunchKernelGGL((unique_kernel<int32_t, THREADS, PER>), dim3((unsigned)num_samples), \
                                dim3(THREADS), 0, stream, view_of<int32_t>(gr), a);                  \
     } while (0)
+    // up to 256 slots one wavefront per sample (its barriers cost nothing), more lanes above
     if (a.W <= 64) ND_UNIQUE_LAUNCH(64, 1);
-    else if (a.W <= 256) ND_UNIQUE_LAUNCH(256, 1);
+    else if (a.W <= 128) ND_UNIQUE_LAUNCH(64, 2);
+    else if (a.W <= 256) ND_UNIQUE_LAUNCH(64, 4);
     else if (a.W <= 512) ND_UNIQUE_LAUNCH(256, 2);
     else if (a.W <= 1024) ND_UNIQUE_LAUNCH(256, 4);
     else ND_UNIQUE_LAUNCH(256, 8);
