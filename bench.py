@@ -225,11 +225,10 @@ def main():
     dom = max(kernel_phases, key=lambda k: phase_ms[k])
     avg_launch_ms = phase_ms[dom] / launches[dom]
     if stats is not None and dom == "sample_sub":
-        # draws made by the sub-wavefront kernel: those of all live pairs minus the share of the
-        # workgroup and grid classes (column 7 of the scheduling statistics)
+        # draws made by the step's sampling kernel: those of all live pairs
         m_per_step = [pkw.get("fanout", [1] * len(s.step_len))[i] if app == B.ND_KHOP else 1
                       for i in range(len(s.step_len))]
-        draws = sum(int(stats[i, 0]) * m_per_step[i] - int(stats[i, 7]) for i in range(len(s.step_len)))
+        draws = sum(int(stats[i, 0]) * m_per_step[i] for i in range(len(s.step_len)))
     else:
         draws = live if dom != "sample_sp" else slots
     draws_per_launch = draws / launches[dom]
@@ -256,8 +255,8 @@ def main():
     hbm_gbs = draws_per_launch * hbm_bytes_per_draw / (avg_launch_ms * 1e-3) / 1e9
     draws_per_s = draws_per_launch / (avg_launch_ms * 1e-3)
     roofline = {
-        "kernel": {"sample_sub": "sample_sub_kernel", "sample_sp": "sample_sp_kernel",
-                   "layer": "layer_kernel", "sample_wg": "sample_wg_kernel"}[dom],
+        "kernel": {"sample_sub": "sample_tp_kernel", "sample_sp": "sample_sp_kernel",
+                   "layer": "layer_kernel", "sample_wg": "sample_tp_kernel"}[dom],
         "bound": "hbm", "achieved": round(hbm_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(hbm_gbs / HBM_PEAK_GBS, 4),
         "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, args.mode, dom)),

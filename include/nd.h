@@ -321,16 +321,15 @@ int nd_samples_pack(const int32_t* const* step_out_dev, int32_t num_steps, const
  * ms[ND_PHASE_COUNT] and intervals[ND_PHASE_COUNT] (the caller zeroes them),
  * and resets the recording.  At most 16384 events are kept between reads;
  * later marks are dropped and nd_profile_read then returns ND_ERR_BAD_ARGUMENT.
- * The sub-wavefront phase and the workgroup/grid phase each contain exactly one
- * kernel launch per step.
+ * The sampling phase contains exactly one kernel launch per step.
  */
 typedef enum nd_phase {
     ND_PHASE_NONE = -1,
     ND_PHASE_INIT = 0,        /* workspace header / bitmap reset                    */
     ND_PHASE_SORT = 1,        /* transit enumeration, NULL fill + radix sort        */
     ND_PHASE_GROUP = 2,       /* segmented scan + classification                    */
-    ND_PHASE_SAMPLE_SUB = 3,  /* sub-wavefront class kernel                         */
-    ND_PHASE_SAMPLE_WG = 4,   /* workgroup and grid class kernel (one launch)       */
+    ND_PHASE_SAMPLE_SUB = 3,  /* the step's sampling kernel (all three classes)     */
+    ND_PHASE_SAMPLE_WG = 4,   /* the same kernel when a heavy class is forced       */
     ND_PHASE_SAMPLE_SP = 5,   /* sample-parallel kernel (ablation mode)             */
     ND_PHASE_LAYER = 6,       /* collective (layer) kernel                          */
     ND_PHASE_UNIQUE = 7,      /* duplicate removal and refill (unique neighbours)   */

@@ -602,7 +602,8 @@ int nd_sample(const nd_graph* h, int app, const nd_params* params, const int32_t
         uint32_t* heavy_bits = sp.force_class == ND_CLASS_AUTO ? (uint32_t*)(ws + pl.o_bits) : nullptr;
         if (!coarse) {
             mark_phase(ND_PHASE_GROUP, stream);
-            rc = build_groups(keys, n_slots, ctl + i, g_key, g_start, (uint32_t*)(ws + pl.o_tiles), stream);
+            rc = build_groups(keys, n_slots, ctl + i, g_key, g_start, (uint32_t*)(ws + pl.o_tiles), heavy_bits,
+                              pl.bit_words, stream);
             if (rc != ND_OK) return rc;
             rc = classify_groups(g_key, g_start, n_slots, ctl + i, sp, list_wg, chunk_gid, chunk_idx,
                                  pl.cap_chunks, heavy_bits, stream);
@@ -742,7 +743,7 @@ int nd_group_by_transit(const int32_t* transits_dev, int64_t n, int64_t V,
     int rc = sort_pairs(transits_dev, n, (int32_t)V, sp, keysA, valsA, keysB, valsB, hist, ctl, nullptr,
                         1, nullptr, &keys, &vals, stream);
     if (rc != ND_OK) return rc;
-    rc = build_groups(keys, n, ctl, group_transit_dev, group_start_dev, tiles, stream);
+    rc = build_groups(keys, n, ctl, group_transit_dev, group_start_dev, tiles, nullptr, 0, stream);
     if (rc != ND_OK) return rc;
     if (n > 0) {
         ND_HIP_CHECK(hipMemcpyAsync(sorted_transits_dev, keys, (size_t)n * 4, hipMemcpyDeviceToDevice, stream));

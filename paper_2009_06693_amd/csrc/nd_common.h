@@ -141,8 +141,10 @@ constexpr int kSegThreads = 256;
 constexpr int kSegItems = 16;
 constexpr int kSegTile = kSegThreads * kSegItems;
 size_t seg_scratch_bytes(int64_t n_slots);
+// heavy_bits (may be null): the per-vertex marks of the previous step are cleared on the way.
 int build_groups(const int32_t* sorted_keys, int64_t max_pairs, StepCtl* ctl, int32_t* g_key,
-                 int32_t* g_start, uint32_t* tile_counts, hipStream_t stream);
+                 int32_t* g_start, uint32_t* tile_counts, uint32_t* heavy_bits, int64_t bit_words,
+                 hipStream_t stream);
 
 struct SchedParams {
     int32_t m;              // draws per pair

@@ -264,7 +264,10 @@ template <int DRAW, bool HEAVY, typename OffT>
 __device__ __forceinline__ void sub_loop(const GraphView<OffT>& g, const DrawArgs& a, uint32_t P,
                                          const int32_t* __restrict__ keys,
                                          const int32_t* __restrict__ vals,
-                                         const uint32_t* heavy_bits, uint32_t pairs_per_block) {
+                                         const uint32_t* heavy_bits, uint32_t pairs_per_block,
+                                         uint32_t tid, uint32_t block, uint32_t blocks) {
+    // tid, block, blocks: position of this lane in a grid of 256-lane groups (four of them share
+    // one workgroup of the launch)
     // independent pairs in flight per lane (the looping draws gain nothing from a second one)
     constexpr int U = DRAW == kDrawUniform ? 2 : 1;
     if (pairs_per_block != 0u) {
@@ -273,11 +276,11 @@ __device__ __forceinline__ void sub_loop(const GraphView<OffT>& g, const DrawArg
         // first draw so that their memory latencies overlap; they are adjacent blocks of the
         // sorted array, so the whole grid works on one contiguous window of transits at a time
         // (that window is what L2 keeps hot).
-        const uint32_t pl = fastdiv(threadIdx.x, a.div_m);
-        const uint32_t jj = threadIdx.x - pl * a.m;
+        const uint32_t pl = fastdiv(tid, a.div_m);
+        const uint32_t jj = tid - pl * a.m;
         if (pl >= pairs_per_block) return;
-        const uint32_t stride = gridDim.x * pairs_per_block * U;
-        uint32_t pi = blockIdx.x * pairs_per_block * U + pl;
+        const uint32_t stride = blocks * pairs_per_block * U;
+        uint32_t pi = block * pairs_per_block * U + pl;
         if (pi >= P) return;
         // Software pipeline, three rounds deep: the sorted pairs of round i + 2 and the row offsets
         // of round i + 1 are requested before round i draws, and round i's stores are issued last,
@@ -311,8 +314,8 @@ __device__ __forceinline__ void sub_loop(const GraphView<OffT>& g, const DrawArg
         }
     } else {
         const uint32_t total = P * a.m;
-        const uint32_t stride = gridDim.x * 256u;
-        for (uint32_t d = blockIdx.x * 256u + threadIdx.x; d < total; d += stride) {
+        const uint32_t stride = blocks * 256u;
+        for (uint32_t d = block * 256u + tid; d < total; d += stride) {
             const uint32_t pi = fastdiv(d, a.div_m);
             const uint32_t jj = d - pi * a.m;
             const PairCtx c = load_pair<HEAVY>(g, keys, vals, heavy_bits, pi, P);
@@ -320,21 +323,6 @@ __device__ __forceinline__ void sub_loop(const GraphView<OffT>& g, const DrawArg
             if (c.mine) a.out[c.q * a.m + jj] = res;
         }
     }
-}
-
-template <int DRAW, typename OffT>
-__global__ __launch_bounds__(256) void sample_sub_kernel(GraphView<OffT> g, DrawArgs a,
-                                                         const StepCtl* __restrict__ ctl,
-                                                         const int32_t* __restrict__ keys,
-                                                         const int32_t* __restrict__ vals,
-                                                         const uint32_t* heavy_bits,
-                                                         uint32_t pairs_per_block) {
-    const uint32_t P = ctl->P;
-    // no transit went to the other classes this step: nothing to look up in the bitmap
-    if (heavy_bits != nullptr && (ctl->n_wg | ctl->n_chunks) != 0u)
-        sub_loop<DRAW, true>(g, a, P, keys, vals, heavy_bits, pairs_per_block);
-    else
-        sub_loop<DRAW, false>(g, a, P, keys, vals, heavy_bits, pairs_per_block);
 }
 
 // ---------------------------------------------------------------- workgroup and grid classes
@@ -388,53 +376,60 @@ __device__ __forceinline__ void workgroup_draws(const GraphView<OffT>& g, const 
     }
 }
 
-// Work items are handed out through a device-side cursor, so workgroups that draw short items
-// take more of them.  Items [0, n_wg) are the workgroup-class transits (one item draws for
-// the whole transit); items [n_wg, n_wg + n_chunks) are the chunks of the grid-class
-// transits (many workgroups share one transit).  Both classes run in this one launch.
+// One launch per step for all three classes.  Every workgroup first serves the workgroup and
+// grid classes: it takes work items from a device-side cursor - items [0, n_wg) are the
+// workgroup-class transits (one workgroup does the whole transit), items [n_wg, n_wg + n_chunks)
+// are the chunks of the grid-class transits (many workgroups share one transit) - until the
+// cursor runs out.  Then it turns into four independent 256-lane groups of the lane-per-draw
+// loop over all pairs (sub-wavefront class), which skips the pairs of transits marked in
+// heavy_bits.  A forced class runs only its half.
 template <int DRAW, typename OffT>
-__global__ __launch_bounds__(kWgThreads) void sample_wg_kernel(GraphView<OffT> g, DrawArgs a,
-                                                               SchedParams sp,
-                                                               StepCtl* __restrict__ ctl,
-                                                               const int32_t* __restrict__ g_key,
-                                                               const int32_t* __restrict__ g_start,
-                                                               const int32_t* __restrict__ vals,
-                                                               const int32_t* __restrict__ list_wg,
-                                                               const int32_t* __restrict__ chunk_gid,
-                                                               const int32_t* __restrict__ chunk_idx,
-                                                               uint32_t cap_wg, uint32_t cap_chunks,
-                                                               uint32_t* __restrict__ heavy_bits) {
+__global__ __launch_bounds__(kWgThreads) void sample_tp_kernel(
+    GraphView<OffT> g, DrawArgs a, SchedParams sp, StepCtl* __restrict__ ctl,
+    const int32_t* __restrict__ keys, const int32_t* __restrict__ vals,
+    const int32_t* __restrict__ g_key, const int32_t* __restrict__ g_start,
+    const int32_t* __restrict__ list_wg, const int32_t* __restrict__ chunk_gid,
+    const int32_t* __restrict__ chunk_idx, uint32_t cap_wg, uint32_t cap_chunks,
+    const uint32_t* __restrict__ heavy_bits, uint32_t pairs_per_block, int do_heavy, int do_lanes) {
     constexpr uint32_t cap = StageCap<DRAW>::value;
     __shared__ int32_t lds_col[cap];
     __shared__ uint64_t lds_cum[DRAW == kDrawWeighted ? cap : 1];
     __shared__ uint32_t lds_wq[DRAW == kDrawNode2vec ? cap : 1];
     __shared__ uint32_t s_item;
-    uint32_t n_wg = ctl->n_wg, n_chunks = ctl->n_chunks;
-    if (n_wg > cap_wg) n_wg = cap_wg;              // the lists are sized so this never bites
-    if (n_chunks > cap_chunks) n_chunks = cap_chunks;
-    const uint32_t n_items = n_wg + n_chunks;
-    for (;;) {
-        if (threadIdx.x == 0) s_item = atomicAdd(&ctl->wg_cursor, 1u);
-        __syncthreads();
-        const uint32_t i = s_item;
-        if (i >= n_items) break;  // uniform: every wave of the workgroup leaves here
-        const bool grid = i >= n_wg;
-        const uint32_t gid = (uint32_t)(grid ? chunk_gid[i - n_wg] : list_wg[i]);
-        const uint32_t size = (uint32_t)(g_start[gid + 1] - g_start[gid]);
-        const uint32_t draws = size * a.m;
-        uint32_t d0 = 0, d1 = draws;
-        if (grid) {
-            d0 = (uint32_t)chunk_idx[i - n_wg] * (uint32_t)sp.wg_max;
-            d1 = d0 + (uint32_t)sp.wg_max < draws ? d0 + (uint32_t)sp.wg_max : draws;
+    if (do_heavy) {
+        uint32_t n_wg = ctl->n_wg, n_chunks = ctl->n_chunks;
+        if (n_wg > cap_wg) n_wg = cap_wg;              // the lists are sized so this never bites
+        if (n_chunks > cap_chunks) n_chunks = cap_chunks;
+        const uint32_t n_items = n_wg + n_chunks;
+        for (;;) {
+            if (threadIdx.x == 0) s_item = atomicAdd(&ctl->wg_cursor, 1u);
+            __syncthreads();
+            const uint32_t i = s_item;
+            if (i >= n_items) break;  // uniform: every wave of the workgroup leaves here
+            const bool grid = i >= n_wg;
+            const uint32_t gid = (uint32_t)(grid ? chunk_gid[i - n_wg] : list_wg[i]);
+            const uint32_t size = (uint32_t)(g_start[gid + 1] - g_start[gid]);
+            const uint32_t draws = size * a.m;
+            uint32_t d0 = 0, d1 = draws;
+            if (grid) {
+                d0 = (uint32_t)chunk_idx[i - n_wg] * (uint32_t)sp.wg_max;
+                d1 = d0 + (uint32_t)sp.wg_max < draws ? d0 + (uint32_t)sp.wg_max : draws;
+            }
+            workgroup_draws<DRAW, OffT>(g, a, ctl, g_key, g_start, vals, gid, d0, d1, lds_col, lds_cum,
+                                        lds_wq);
+            __syncthreads();  // s_item and the LDS copy are rewritten by the next item
         }
-        workgroup_draws<DRAW, OffT>(g, a, ctl, g_key, g_start, vals, gid, d0, d1, lds_col, lds_cum,
-                                    lds_wq);
-        // un-mark the transit for the next step (the sub-wavefront kernel of this step is done)
-        if (threadIdx.x == 0 && d0 == 0 && heavy_bits != nullptr) {
-            const uint32_t v = (uint32_t)g_key[gid];
-            atomicAnd(&heavy_bits[v >> 5], ~(1u << (v & 31u)));
-        }
-        __syncthreads();  // s_item and the LDS copy are rewritten by the next item
+    }
+    if (do_lanes) {  // no barrier from here on
+        const uint32_t P = ctl->P;
+        const uint32_t tid = threadIdx.x & 255u;
+        const uint32_t block = blockIdx.x * (kWgThreads / 256) + (threadIdx.x >> 8);
+        const uint32_t blocks = gridDim.x * (kWgThreads / 256);
+        // no transit went to the other classes this step: nothing to look up in the bitmap
+        if (heavy_bits != nullptr && (ctl->n_wg | ctl->n_chunks) != 0u)
+            sub_loop<DRAW, true>(g, a, P, keys, vals, heavy_bits, pairs_per_block, tid, block, blocks);
+        else
+            sub_loop<DRAW, false>(g, a, P, keys, vals, heavy_bits, pairs_per_block, tid, block, blocks);
     }
 }
 
@@ -442,29 +437,24 @@ template <int DRAW, typename OffT>
 int launch_tp(const Graph& gr, const DrawArgs& a, const SchedParams& sp, const TpStep& t,
               hipStream_t stream) {
     const GraphView<OffT> g = view_of<OffT>(gr);
-    // sub-wavefront class: grid-stride over the draws of the live pairs
-    if (sp.force_class == ND_CLASS_AUTO || sp.force_class == ND_CLASS_SUBWAVE) {
-        int64_t blocks = (t.max_draws + 255) / 256;
-        const int64_t persistent = (int64_t)gr.num_cus * 8;  // 8 waves per SIMD
-        blocks = blocks < 1 ? 1 : (blocks > persistent ? persistent : blocks);
-        mark_phase(ND_PHASE_SAMPLE_SUB, stream);
-        // whole pairs per 256-lane round when that idles under a tenth of the lanes
-        uint32_t ppb = a.m <= 256u ? 256u / a.m : 0u;
-        if (ppb * a.m < 231u) ppb = 0u;
-        hipLaunchKernelGGL((sample_sub_kernel<DRAW, OffT>), dim3((unsigned)blocks), dim3(256), 0,
-                           stream, g, a, t.ctl, t.keys, t.vals,
-                           sp.force_class == ND_CLASS_AUTO ? (const uint32_t*)t.heavy_bits : nullptr,
-                           ppb);
-    }
-    if (sp.force_class != ND_CLASS_SUBWAVE) {
-        const int64_t wg_persistent = (int64_t)gr.num_cus * 2;
-        int64_t blocks = t.max_wg + t.max_chunks;
-        blocks = blocks < 1 ? 1 : (blocks > wg_persistent ? wg_persistent : blocks);
-        mark_phase(ND_PHASE_SAMPLE_WG, stream);
-        hipLaunchKernelGGL((sample_wg_kernel<DRAW, OffT>), dim3((unsigned)blocks), dim3(kWgThreads), 0,
-                           stream, g, a, sp, t.ctl, t.g_key, t.g_start, t.vals, t.list_wg, t.chunk_gid,
-                           t.chunk_idx, (uint32_t)t.cap_wg, (uint32_t)t.cap_chunks, t.heavy_bits);
-    }
+    const bool lanes = sp.force_class == ND_CLASS_AUTO || sp.force_class == ND_CLASS_SUBWAVE;
+    const bool heavy = sp.force_class != ND_CLASS_SUBWAVE;
+    // Workgroups that are all resident at once (two per CU: 8 waves per SIMD), fewer when the
+    // step is small: one per 1,024 draws for the lane-per-draw part, one per heavy item.
+    const int64_t places = (int64_t)gr.num_cus * 2;
+    int64_t blocks = 1;
+    if (lanes) blocks = (t.max_draws + kWgThreads - 1) / kWgThreads;
+    if (heavy && t.max_wg + t.max_chunks > blocks) blocks = t.max_wg + t.max_chunks;
+    blocks = blocks < 1 ? 1 : (blocks > places ? places : blocks);
+    // whole pairs per 256-lane round when that idles under a tenth of the lanes
+    uint32_t ppb = a.m <= 256u ? 256u / a.m : 0u;
+    if (ppb * a.m < 231u) ppb = 0u;
+    mark_phase(lanes ? ND_PHASE_SAMPLE_SUB : ND_PHASE_SAMPLE_WG, stream);
+    hipLaunchKernelGGL((sample_tp_kernel<DRAW, OffT>), dim3((unsigned)blocks), dim3(kWgThreads), 0,
+                       stream, g, a, sp, t.ctl, t.keys, t.vals, t.g_key, t.g_start, t.list_wg,
+                       t.chunk_gid, t.chunk_idx, (uint32_t)t.cap_wg, (uint32_t)t.cap_chunks,
+                       sp.force_class == ND_CLASS_AUTO ? (const uint32_t*)t.heavy_bits : nullptr, ppb,
+                       heavy ? 1 : 0, lanes ? 1 : 0);
     ND_HIP_CHECK(hipGetLastError());
     return ND_OK;
 }

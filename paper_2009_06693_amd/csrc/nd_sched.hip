@@ -35,8 +35,15 @@ __device__ __forceinline__ bool is_head(const int32_t* __restrict__ keys, int64_
 // with the last key of the lane before.
 __global__ __launch_bounds__(kSegThreads) void seg_count_kernel(const int32_t* __restrict__ keys,
                                                                 const StepCtl* __restrict__ ctl,
-                                                                uint32_t* __restrict__ wave_counts) {
+                                                                uint32_t* __restrict__ wave_counts,
+                                                                uint32_t* __restrict__ heavy_bits,
+                                                                int64_t bit_words) {
     const int lane = lane_id(), wave = wave_id();
+    // the marks of the previous step's heavy transits go (this step's are set by classify_kernel)
+    if (heavy_bits != nullptr)
+        for (int64_t w = (int64_t)blockIdx.x * kSegThreads + threadIdx.x; w < bit_words;
+             w += (int64_t)gridDim.x * kSegThreads)
+            heavy_bits[w] = 0u;
     const int64_t P = ctl->P;
     const int64_t base = (int64_t)blockIdx.x * kSegTile + (int64_t)wave * kSegPerWave;
     uint32_t cnt = 0;
@@ -126,9 +133,13 @@ constexpr int64_t kSegSmallLimit = 8192;
 __global__ __launch_bounds__(1024) void seg_small_kernel(const int32_t* __restrict__ keys,
                                                          StepCtl* __restrict__ ctl,
                                                          int32_t* __restrict__ g_key,
-                                                         int32_t* __restrict__ g_start) {
+                                                         int32_t* __restrict__ g_start,
+                                                         uint32_t* __restrict__ heavy_bits,
+                                                         int64_t bit_words) {
     __shared__ uint32_t wsum[16];
     const int lane = lane_id(), wave = wave_id();
+    if (heavy_bits != nullptr)  // the marks of the previous step's heavy transits go
+        for (int64_t w = threadIdx.x; w < bit_words; w += 1024) heavy_bits[w] = 0u;
     const int64_t P = ctl->P;
     const int64_t per_wave = ((P + 15) / 16 + 63) / 64 * 64;
     const int64_t wb = (int64_t)wave * per_wave;
@@ -261,16 +272,18 @@ __global__ __launch_bounds__(256) void classify_kernel(const int32_t* __restrict
 }  // namespace
 
 int build_groups(const int32_t* sorted_keys, int64_t max_pairs, StepCtl* ctl, int32_t* g_key,
-                 int32_t* g_start, uint32_t* tile_counts, hipStream_t stream) {
+                 int32_t* g_start, uint32_t* tile_counts, uint32_t* heavy_bits, int64_t bit_words,
+                 hipStream_t stream) {
     if (max_pairs <= kSegSmallLimit) {
-        hipLaunchKernelGGL(seg_small_kernel, dim3(1), dim3(1024), 0, stream, sorted_keys, ctl, g_key, g_start);
+        hipLaunchKernelGGL(seg_small_kernel, dim3(1), dim3(1024), 0, stream, sorted_keys, ctl, g_key, g_start,
+                           heavy_bits, bit_words);
         ND_HIP_CHECK(hipGetLastError());
         return ND_OK;
     }
     int64_t tiles = (max_pairs + kSegTile - 1) / kSegTile;
     if (tiles < 1) tiles = 1;
     hipLaunchKernelGGL(seg_count_kernel, dim3((unsigned)tiles), dim3(kSegThreads), 0, stream,
-                       sorted_keys, ctl, tile_counts);
+                       sorted_keys, ctl, tile_counts, heavy_bits, bit_words);
     hipLaunchKernelGGL(seg_scan_kernel, dim3(1), dim3(1024), 0, stream, tile_counts,
                        tiles * (kSegThreads / 64), ctl, g_start);
     hipLaunchKernelGGL(seg_write_kernel, dim3((unsigned)tiles), dim3(kSegThreads), 0, stream,
