@@ -71,19 +71,23 @@ __global__ __launch_bounds__(kSegThreads) void seg_count_kernel(const int32_t* _
     if (lane == 63) wave_counts[(int64_t)blockIdx.x * kSegWaves + wave] = incl;
 }
 
-// One workgroup: exclusive scan of the per-wavefront head counts in place, publishes
-// the number of groups and resets the class counters of the step.
-__global__ __launch_bounds__(1024) void seg_scan_kernel(uint32_t* __restrict__ tile_counts,
+// One workgroup: exclusive scan of the per-wavefront head counts in place (a thread takes the
+// four counts of one tile), publishes the number of groups and resets the class counters of
+// the step.
+static_assert(kSegWaves == 4, "seg_scan_kernel reads one tile's counts as a uint4");
+__global__ __launch_bounds__(1024) void seg_scan_kernel(uint32_t* __restrict__ wave_counts,
                                                         int64_t num_tiles, StepCtl* __restrict__ ctl,
                                                         int32_t* __restrict__ g_start) {
     __shared__ uint32_t tmp[18];
     uint32_t carry = 0;
     for (int64_t base = 0; base < num_tiles; base += 1024) {
         const int64_t i = base + threadIdx.x;
-        const uint32_t x = i < num_tiles ? tile_counts[i] : 0u;
+        uint4 c = make_uint4(0u, 0u, 0u, 0u);
+        if (i < num_tiles) c = reinterpret_cast<const uint4*>(wave_counts)[i];
         uint32_t total;
-        const uint32_t ex = block_exclusive_scan<uint32_t, 1024>(x, tmp, &total);
-        if (i < num_tiles) tile_counts[i] = carry + ex;
+        const uint32_t ex = carry + block_exclusive_scan<uint32_t, 1024>(c.x + c.y + c.z + c.w, tmp, &total);
+        if (i < num_tiles)
+            reinterpret_cast<uint4*>(wave_counts)[i] = make_uint4(ex, ex + c.x, ex + c.x + c.y, ex + c.x + c.y + c.z);
         carry += total;
         __syncthreads();
     }
@@ -284,8 +288,7 @@ int build_groups(const int32_t* sorted_keys, int64_t max_pairs, StepCtl* ctl, in
     if (tiles < 1) tiles = 1;
     hipLaunchKernelGGL(seg_count_kernel, dim3((unsigned)tiles), dim3(kSegThreads), 0, stream,
                        sorted_keys, ctl, tile_counts, heavy_bits, bit_words);
-    hipLaunchKernelGGL(seg_scan_kernel, dim3(1), dim3(1024), 0, stream, tile_counts,
-                       tiles * (kSegThreads / 64), ctl, g_start);
+    hipLaunchKernelGGL(seg_scan_kernel, dim3(1), dim3(1024), 0, stream, tile_counts, tiles, ctl, g_start);
     hipLaunchKernelGGL(seg_write_kernel, dim3((unsigned)tiles), dim3(kSegThreads), 0, stream,
                        sorted_keys, ctl, tile_counts, g_key, g_start);
     ND_HIP_CHECK(hipGetLastError());
