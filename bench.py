@@ -31,7 +31,7 @@ PHILOX_ONLY_DRAWS_PER_S = 8.0e11
 # WRITE_SIZE; scaled by the factors a 1 GiB copy kernel gives: x2.0 and x1.0), averaged over the
 # launches of one call.  Source: profiles/c5_khop_tp_rocprofv3.md.  None where not profiled.
 MEASURED_TRAFFIC_BYTES = {
-    ("c5_khop", "tp", "sample_sub"): int((355.0 + 2120.3 + 405.1 + 2680.5) / 2 * 1048576),
+    ("c5_khop", "tp", "sample_sub"): int((281.4 + 2313.6 + 402.9 + 2918.0) / 2 * 1048576),
 }
 
 WORKLOADS = {
