@@ -390,8 +390,7 @@ __global__ __launch_bounds__(kWgThreads) void sample_tp_kernel(
     const int32_t* __restrict__ g_key, const int32_t* __restrict__ g_start,
     const int32_t* __restrict__ list_wg, const int32_t* __restrict__ chunk_gid,
     const int32_t* __restrict__ chunk_idx, uint32_t cap_wg, uint32_t cap_chunks,
-    const uint32_t* __restrict__ heavy_bits, uint32_t pairs_per_block, int do_heavy, int do_lanes,
-    int spread) {
+    const uint32_t* __restrict__ heavy_bits, uint32_t pairs_per_block, int do_heavy, int do_lanes) {
     constexpr uint32_t cap = StageCap<DRAW>::value;
     __shared__ int32_t lds_col[cap];
     __shared__ uint64_t lds_cum[DRAW == kDrawWeighted ? cap : 1];
@@ -424,12 +423,11 @@ __global__ __launch_bounds__(kWgThreads) void sample_tp_kernel(
     if (do_lanes) {  // no barrier from here on
         const uint32_t P = ctl->P;
         const uint32_t tid = threadIdx.x & 255u;
-        // Four 256-lane groups per workgroup.  With plenty of rounds a workgroup's groups take
-        // neighbouring rounds (they share cache lines); with fewer rounds than groups the
-        // rounds are dealt to the workgroups first, so that a small step still uses every CU.
+        // Four 256-lane groups per workgroup; group i of workgroup b is number i * gridDim.x + b,
+        // so that neighbouring rounds go to different workgroups (CUs) and a small step still
+        // uses every CU.
         const uint32_t blocks = gridDim.x * (kWgThreads / 256);
-        const uint32_t block = spread ? (threadIdx.x >> 8) * gridDim.x + blockIdx.x
-                                      : blockIdx.x * (kWgThreads / 256) + (threadIdx.x >> 8);
+        const uint32_t block = (threadIdx.x >> 8) * gridDim.x + blockIdx.x;
         // no transit went to the other classes this step: nothing to look up in the bitmap
         if (heavy_bits != nullptr && (ctl->n_wg | ctl->n_chunks) != 0u)
             sub_loop<DRAW, true>(g, a, P, keys, vals, heavy_bits, pairs_per_block, tid, block, blocks);
@@ -449,8 +447,7 @@ int launch_tp(const Graph& gr, const DrawArgs& a, const SchedParams& sp, const T
     const int64_t places = (int64_t)gr.num_cus * 2;
     int64_t blocks = 1;
     const int64_t rounds = (t.max_draws + 255) / 256;   // upper bound
-    const bool spread = rounds < places * (kWgThreads / 256);
-    if (lanes) blocks = spread ? rounds : places;
+    if (lanes) blocks = rounds < places ? rounds : places;
     if (heavy && t.max_wg + t.max_chunks > blocks) blocks = t.max_wg + t.max_chunks;
     blocks = blocks < 1 ? 1 : (blocks > places ? places : blocks);
     // whole pairs per 256-lane round when that idles under a tenth of the lanes
@@ -461,7 +458,7 @@ int launch_tp(const Graph& gr, const DrawArgs& a, const SchedParams& sp, const T
                        stream, g, a, sp, t.ctl, t.keys, t.vals, t.g_key, t.g_start, t.list_wg,
                        t.chunk_gid, t.chunk_idx, (uint32_t)t.cap_wg, (uint32_t)t.cap_chunks,
                        sp.force_class == ND_CLASS_AUTO ? (const uint32_t*)t.heavy_bits : nullptr, ppb,
-                       heavy ? 1 : 0, lanes ? 1 : 0, spread ? 1 : 0);
+                       heavy ? 1 : 0, lanes ? 1 : 0);
     ND_HIP_CHECK(hipGetLastError());
     return ND_OK;
 }
