@@ -24,7 +24,9 @@ namespace nd {
 
 namespace {
 
-constexpr int kLayerThreads = 256;
+// 512 lanes per sample: the transits' 24 bytes each of LDS allow three workgroups per CU, and the
+// draws are chains of dependent reads, so the wider workgroup (24 waves per CU) hides more latency
+constexpr int kLayerThreads = 512;
 
 // Exact floor(num / c) for num < 2^24 * c: the quotient is estimated in double precision
 // (relative error 2^-52, so off by at most one for a quotient below 2^24) and corrected with
