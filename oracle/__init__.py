@@ -71,6 +71,8 @@ def _load():
         L.ndo_khop_unique.argtypes = [vp, vp, i32, i32, vp, i64, u64, u64, vp]
         L.ndo_layer.restype = ctypes.c_int
         L.ndo_layer.argtypes = [vp, i32, vp, i32, vp, i64, u64, u64, vp]
+        L.ndo_layer_weighted.restype = ctypes.c_int
+        L.ndo_layer_weighted.argtypes = [vp, i32, vp, i32, vp, i64, u64, u64, vp]
         L.ndo_layer_edges.restype = ctypes.c_int
         L.ndo_layer_edges.argtypes = [vp, vp, i32, vp, i32, i64, vp, vp, i64]
         _lib = L
@@ -199,17 +201,20 @@ def khop(g: OracleGraph, roots, fanout, seed: int, sample_id_base: int = 0, uniq
     return res
 
 
-def layer(g: OracleGraph, roots, roots_per_sample: int, fanout, seed: int, sample_id_base: int = 0):
+def layer(g: OracleGraph, roots, roots_per_sample: int, fanout, seed: int, sample_id_base: int = 0,
+          use_weights: bool = False):
     """`roots` holds num_samples * roots_per_sample vertices; returns one int32
-    [num_samples, fanout[i]] array per step."""
+    [num_samples, fanout[i]] array per step.  use_weights: draw in proportion to the graph's edge
+    weights instead of 1 / deg(transit)^2."""
     r = _roots(roots)
     f = np.ascontiguousarray(fanout, dtype=np.int32)
     if r.shape[0] % roots_per_sample:
         raise ValueError("roots must be a whole number of samples")
     B = r.shape[0] // roots_per_sample
     out = np.empty(int(B * f.astype(np.int64).sum()), dtype=np.int32)
-    _check(_load().ndo_layer(g._h, roots_per_sample, f.ctypes.data, f.shape[0], r.ctypes.data, B,
-                             sample_id_base, seed, out.ctypes.data), "layer")
+    fn = _load().ndo_layer_weighted if use_weights else _load().ndo_layer
+    _check(fn(g._h, roots_per_sample, f.ctypes.data, f.shape[0], r.ctypes.data, B,
+              sample_id_base, seed, out.ctypes.data), "layer")
     res, base = [], 0
     for m in f:
         res.append(out[base:base + B * int(m)].reshape(B, int(m)))

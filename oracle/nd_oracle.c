@@ -509,6 +509,65 @@ int ndo_layer(const ndo_graph* g, int32_t roots_per_sample, const int32_t* fanou
 }
 
 /* ------------------------------------------------------------------------ */
+/* Layer sampling with the graph's own edge weights: an entry of the         */
+/* combined neighbourhood that comes from transit v and points to u carries  */
+/* the quantised weight w_q(v,u), so u is drawn with probability             */
+/* proportional to the sum of w(v,u) over the transit rows that contain u.   */
+/* With w(v,u) = 1 / (deg(v) deg(u)) this is the squared column norm of the  */
+/* symmetrically normalised adjacency matrix restricted to the transit rows  */
+/* (the LADIES criterion; Section 4.2 leaves the criterion to `next`).       */
+/* Same inverse transform as above: x = floor(r64 * total / 2^64), total =   */
+/* sum over transits of the row's weight sum; inside the chosen row the      */
+/* first entry whose running sum exceeds what is left of x.                  */
+/* ------------------------------------------------------------------------ */
+int ndo_layer_weighted(const ndo_graph* g, int32_t roots_per_sample, const int32_t* fanout, int32_t k,
+                       const int32_t* roots, int64_t num_samples, uint64_t sample_id_base,
+                       uint64_t seed, int32_t* out) {
+    if (!g->cumq) return -5;
+    int64_t step_base = 0;
+    const int32_t* prev = roots;
+    int64_t n_prev = roots_per_sample;
+    for (int32_t i = 0; i < k; ++i) {
+        const int64_t m = fanout[i];
+        if (m < 1) return -2;
+        int32_t* cur = out + step_base;
+        for (int64_t b = 0; b < num_samples; ++b) {
+            const int32_t* transits = prev + b * n_prev;
+            uint64_t total = 0;
+            for (int64_t t = 0; t < n_prev; ++t) {
+                const int32_t v = transits[t];
+                if (!valid_vertex(g, v) || degree(g, v) == 0) continue;
+                total += g->cumq[g->off[v + 1] - 1];
+            }
+            for (int64_t j = 0; j < m; ++j) {
+                int32_t next = NDO_NULL;
+                if (total > 0) {
+                    uint32_t r[4];
+                    draw4(seed, (uint32_t)(sample_id_base + (uint64_t)b), (uint32_t)j, (uint32_t)i, 0u, r);
+                    const uint64_t x = ndo_mulhi64(((uint64_t)r[0] << 32) | r[1], total);
+                    uint64_t before = 0; /* weight of the lists in front of the current one */
+                    for (int64_t t = 0; t < n_prev && next == NDO_NULL; ++t) {
+                        const int32_t v = transits[t];
+                        if (!valid_vertex(g, v) || degree(g, v) == 0) continue;
+                        const uint64_t row = g->cumq[g->off[v + 1] - 1];
+                        if (before + row > x) {
+                            for (int64_t e = g->off[v]; e < g->off[v + 1]; ++e)
+                                if (g->cumq[e] > x - before) { next = g->col[e]; break; }
+                        }
+                        before += row;
+                    }
+                }
+                cur[b * m + j] = next;
+            }
+        }
+        prev = cur;
+        n_prev = m;
+        step_base += num_samples * m;
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------ */
 /* Edges between consecutive layers (Section 4.2, "Importance Sampling": a   */
 /* sample records the edges between the transit vertices of a step and the   */
 /* vertices the step adds).  For sample b, transit slot t and new slot j the */

@@ -305,3 +305,88 @@ def test_unique_exhausts_small_neighbourhoods():
         live = sorted(int(v) for v in out[0][s] if v >= 0)
         assert live == [1, 2]
         assert (out[1][s] == -1).all()          # 1 and 2 have no out-edges; NULL parents give NULL
+
+
+# ----------------------------------------------------------------------------- layer over edge weights
+def _weighted_layer_graph():
+    # directed, weights chosen by hand; vertex 4 is a dead end, vertex 5 is nobody's transit below
+    edges = [(0, 1), (0, 2), (0, 5), (1, 0), (1, 3), (2, 1), (2, 3), (2, 4), (2, 5), (3, 2), (5, 0)]
+    w = [1.0, 2.5, 4.0, 1.5, 1.5, 3.0, 1.0, 2.0, 1.25, 4.5, 2.0]
+    return inputs.from_edges(6, edges, weights=w)
+
+
+def test_weighted_layer_with_one_transit_is_the_weighted_walk_draw():
+    """One transit per sample: the combined neighbourhood is that vertex's list, so the draw is the
+    inverse-transform draw of the weighted walk (pinned on its own) with the same random words."""
+    g = inputs.small_graph(8, 2000, seed=9, weighted=True)
+    og = _og(g)
+    roots = np.arange(g.V, dtype=np.int32)
+    m = 6
+    out = oracle.layer(og, roots, 1, [m], seed=77, sample_id_base=5, use_weights=True)[0]
+    deg = np.diff(g.row_offsets)
+    for b in range(g.V):
+        for j in range(m):
+            if deg[b] == 0:
+                assert out[b, j] == -1
+                continue
+            r = oracle.draw(77, 5 + b, j, 0)
+            e = og.weighted_index(b, int(r[0]), int(r[1]))
+            assert out[b, j] == g.col_indices[g.row_offsets[b] + e]
+
+
+def test_weighted_layer_brute_force_distribution():
+    g = _weighted_layer_graph()
+    og = _og(g)
+    batch = np.array([0, 2, -1, 2, 4, 1], dtype=np.int32)   # a repeat, a NULL and a dead end
+    m = 300000
+    out = oracle.layer(og, batch, batch.size, [m], seed=31, use_weights=True)[0].reshape(-1)
+    wq = np.floor(g.weights.astype(np.float64) * 65536.0 + 0.5)
+    mass = np.zeros(g.V)
+    for t in batch:
+        if t < 0:
+            continue
+        for e in range(g.row_offsets[t], g.row_offsets[t + 1]):
+            mass[g.col_indices[e]] += wq[e]
+    prob = mass / mass.sum()
+    counts = np.bincount(out, minlength=g.V)
+    assert (counts[prob == 0] == 0).all() and (out >= 0).all()
+    keep = prob > 0
+    assert stats.chisquare(counts[keep], prob[keep] * counts.sum()).pvalue > 1e-4
+    # by hand: transits 0, 2, 2, 1 contribute; vertex 3 gets 1.0 twice (from 2) and 1.5 (from 1)
+    assert np.isclose(prob[3], (2 * 1.0 + 1.5) / (7.5 + 2 * 7.25 + 3.0))
+
+
+def test_weighted_layer_walks_down_the_concatenation():
+    """Sorted by the random number, the draws of one sample walk through the transits' lists in slot
+    order and through every list from front to back."""
+    g = _weighted_layer_graph()
+    og = _og(g)
+    batch = np.array([2, 0, 1], dtype=np.int32)
+    m = 4000
+    out = oracle.layer(og, batch, 3, [m], seed=8, use_weights=True)[0].reshape(-1)
+    r64 = np.array([(int(oracle.draw(8, 0, j, 0)[0]) << 32) | int(oracle.draw(8, 0, j, 0)[1]) for j in range(m)],
+                   dtype=np.uint64)
+    seq = out[np.argsort(r64, kind="stable")]
+    concat = np.concatenate([g.col_indices[g.row_offsets[t]:g.row_offsets[t + 1]] for t in batch])
+    # the sorted draws, with repeats squeezed out, spell the concatenation
+    squeezed = seq[np.concatenate([[True], seq[1:] != seq[:-1]])]
+    assert squeezed.tolist() == concat.tolist()
+
+
+def test_weighted_layer_needs_weights():
+    g = inputs.small_graph(6, 200, seed=1)
+    with pytest.raises(Exception):
+        oracle.layer(_og(g), np.arange(8, dtype=np.int32), 4, [3], seed=1, use_weights=True)
+
+
+def test_weighted_layer_boundaries_with_tiny_integer_weights():
+    """Weights of 1, 2 and 1 quanta: x takes the values 0..3 with equal probability, so the three
+    neighbours must come up with probabilities 1/4, 1/2, 1/4 - a draw that lands on a running sum
+    belongs to the next entry."""
+    q = 1.0 / 65536.0
+    g = inputs.from_edges(4, [(0, 1), (0, 2), (0, 3)], weights=[q, 2 * q, q])
+    og = _og(g)
+    m = 200000
+    out = oracle.layer(og, np.zeros(1, dtype=np.int32), 1, [m], seed=5, use_weights=True)[0].reshape(-1)
+    counts = np.bincount(out, minlength=4)[1:]
+    assert stats.chisquare(counts, np.array([0.25, 0.5, 0.25]) * m).pvalue > 1e-4

@@ -49,6 +49,12 @@ MUTANTS = {
                                          "row_ptr[b * n_prev + t] = n_edges + (t > 0);\n            const int32_t tv"),
     "edges_first_samples_list_reused": ("const int32_t v = sampled[b * m + j];\n            if (v == NDO_NULL) continue;",
                                         "const int32_t v = sampled[j];\n            if (v == NDO_NULL) continue;"),
+    "weighted_layer_lists_in_front_forgotten": ("if (g->cumq[e] > x - before) { next = g->col[e]; break; }",
+                                                "if (g->cumq[e] > x) { next = g->col[e]; break; }"),
+    "weighted_layer_boundary": ("if (g->cumq[e] > x - before) { next = g->col[e]; break; }",
+                                "if (g->cumq[e] >= x - before) { next = g->col[e]; break; }"),
+    "weighted_layer_total_misses_the_last_entry": ("total += g->cumq[g->off[v + 1] - 1];",
+                                                   "total += g->off[v + 1] - 2 >= g->off[v] ? g->cumq[g->off[v + 1] - 2] : g->cumq[g->off[v + 1] - 1];"),
     "layer_weight_not_squared": ("total += d * ((((uint64_t)1) << 48) / (d * d));", "total += d * ((((uint64_t)1) << 48) / d);"),
     "layer_index_ignores_lists_in_front": ("(int64_t)((x - before) / c)", "(int64_t)((x / c) % d)"),
     "layer_total_drops_first_transit": ("for (int64_t t = 0; t < n_prev; ++t) {\n                const int32_t v = transits[t];\n                if (!valid_vertex(g, v)) continue;\n                const uint64_t d = (uint64_t)degree(g, v);\n                if (d == 0) continue;\n                if (d >= (1u << 24)) return -4;",
