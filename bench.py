@@ -56,6 +56,10 @@ WORKLOADS = {
                    "multi-dimensional walk, 100 roots per sample, length 100, 41,943 samples, R-MAT scale 22"),
     "c4_layer": ("config4_graph", "layer", dict(num_steps=2, fanout=[2048, 2048], roots_per_sample=64),
                  "layer sampling 64 roots, 2 x 2,048, 4,096 batches, 3M power-law"),
+    "c4_layer_symmetric": ("config4_graph", "layer",
+                           dict(num_steps=2, fanout=[2048, 2048], roots_per_sample=64, use_weights=1),
+                           "layer sampling over edge weights 2^14 / (deg(v) deg(u)) (symmetric normalisation), "
+                           "64 roots, 2 x 2,048, 4,096 batches, 3M power-law"),
 }
 
 
@@ -173,6 +177,11 @@ def main():
            "layer": B.ND_LAYER, "multirw": B.ND_MULTIRW}[app_name]
     t0 = time.time()
     g = getattr(inputs, builder)()
+    if args.workload == "c4_layer_symmetric":
+        deg = np.diff(g.row_offsets).astype(np.float64)
+        src = np.repeat(np.arange(g.V), np.diff(g.row_offsets))
+        g.weights = (16384.0 / (deg[src] * deg[g.col_indices])).astype(np.float32)
+        del src
     sys.stderr.write(f"[bench] {g.describe()} (generated in {time.time() - t0:.1f}s)\n")
     dg = B.nd_graph_create(g.row_offsets, g.col_indices, g.weights)
     if app == B.ND_LAYER:
@@ -295,7 +304,8 @@ def main():
                 o = list(oracle.node2vec(og, r, pkw["num_steps"], pkw["p"], pkw["q"], seed, use_weights=w,
                                          sample_id_base=base))
             else:
-                o = oracle.layer(og, r, pkw["roots_per_sample"], pkw["fanout"], seed, sample_id_base=base)
+                o = oracle.layer(og, r, pkw["roots_per_sample"], pkw["fanout"], seed, sample_id_base=base,
+                                 use_weights=w)
             dt = time.perf_counter() - t
             return sum(int((x >= 0).sum()) for x in o), dt, o
 

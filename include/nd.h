@@ -93,7 +93,10 @@ typedef struct nd_params {
                                /* of entries used in fanout[]                          */
     int32_t fanout[ND_MAX_FANOUT_STEPS]; /* k-hop: neighbours per transit; layer:     */
                                /* vertices per sample, at each step                    */
-    int32_t use_weights;       /* walks: draw proportionally to the edge weight        */
+    int32_t use_weights;       /* walks: draw proportionally to the edge weight; layer: */
+                               /* an entry of the combined neighbourhood weighs its edge */
+                               /* weight instead of 1 / deg(transit)^2 (with weights     */
+                               /* 1 / (deg(v) deg(u)): symmetric normalisation)          */
     int32_t bias_convention;   /* node2vec: 0 = return 1/p, common neighbour 1,        */
                                /* farther 1/q (the node2vec definition); 1 = p, 1/q, 1 */
                                /* (the wording of Section 4.2)                         */

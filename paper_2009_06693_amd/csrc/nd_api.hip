@@ -90,8 +90,8 @@ int check_params(const Graph& g, int app, const nd_params* p, int64_t num_roots,
         set_error("use_weights set but the graph was created without weights");
         return ND_ERR_NO_WEIGHTS;
     }
-    if (p->use_weights && (!walk || app == ND_MULTIRW)) {
-        set_error("use_weights applies to DeepWalk, PPR and node2vec only");
+    if (p->use_weights && app != ND_LAYER && (!walk || app == ND_MULTIRW)) {
+        set_error("use_weights applies to DeepWalk, PPR, node2vec and layer sampling only");
         return ND_ERR_BAD_ARGUMENT;
     }
     if (p->sched_force_class < ND_CLASS_AUTO || p->sched_force_class > ND_CLASS_GRID ||
@@ -501,6 +501,7 @@ int nd_sample(const nd_graph* h, int app, const nd_params* params, const int32_t
             a.transits = i == 0 ? roots_dev : step_out_dev[i - 1];
             a.out = step_out_dev[i];
             a.check_roots = i == 0;
+            a.use_weights = params->use_weights;
             a.status = &hdr->status;
             mark_phase(ND_PHASE_LAYER, stream);
             rc = layer_step(g, a, pl.S, stream);

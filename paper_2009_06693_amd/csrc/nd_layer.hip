@@ -44,7 +44,10 @@ __device__ __forceinline__ uint64_t div_small_quotient(uint64_t num, uint64_t c)
 
 // Dynamic LDS: per transit slot the running sum of masses, the weight c(v) and the first
 // adjacency entry of the transit (24 bytes), so a draw touches global memory once.
-template <typename OffT>
+// WEIGHTED: an entry from transit v to u weighs the graph's quantised edge weight w_q(v,u); the
+// mass of a transit is its row's weight sum and the place inside the row is found by a search
+// over the row's running sums (global memory).
+template <typename OffT, bool WEIGHTED>
 __global__ __launch_bounds__(kLayerThreads) void layer_kernel(GraphView<OffT> g, LayerArgs a) {
     extern __shared__ uint64_t lds[];
     uint64_t* s_incl = lds;
@@ -69,8 +72,13 @@ __global__ __launch_bounds__(kLayerThreads) void layer_kernel(GraphView<OffT> g,
                 rs = (uint64_t)g.off[v];
                 const uint64_t deg = (uint64_t)g.off[v + 1] - rs;
                 if (deg > 0) {
-                    c = (1ull << 48) / (deg * deg);
-                    mass = deg * c;
+                    if (WEIGHTED) {
+                        c = deg;  // the row length takes the weight's place
+                        mass = g.cumq[rs + deg - 1];
+                    } else {
+                        c = (1ull << 48) / (deg * deg);
+                        mass = deg * c;
+                    }
                 }
             }
         }
@@ -99,7 +107,20 @@ __global__ __launch_bounds__(kLayerThreads) void layer_kernel(GraphView<OffT> g,
                 else lo = mid + 1;
             }
             const uint64_t before = lo ? s_incl[lo - 1] : 0ull;
-            const uint64_t idx = div_small_quotient(x - before, s_c[lo]);
+            uint64_t idx;
+            if (WEIGHTED) {  // first entry of the row whose running sum exceeds what is left of x
+                const uint64_t* cum = g.cumq + s_rs[lo];
+                const uint64_t rest = x - before;
+                uint64_t l = 0, h = s_c[lo] - 1;
+                while (l < h) {
+                    const uint64_t mid = (l + h) >> 1;
+                    if (cum[mid] > rest) h = mid;
+                    else l = mid + 1;
+                }
+                idx = l;
+            } else {
+                idx = div_small_quotient(x - before, s_c[lo]);
+            }
             res = g.col[s_rs[lo] + idx];
         }
         a.out[(uint64_t)b * a.m + j] = res;
@@ -111,22 +132,23 @@ __global__ __launch_bounds__(kLayerThreads) void layer_kernel(GraphView<OffT> g,
 int layer_step(const Graph& gr, const LayerArgs& a, int64_t num_samples, hipStream_t stream) {
     if (num_samples == 0) return ND_OK;
     const size_t lds_bytes = (size_t)a.n_prev * 24;  // at most 96 KB of the 160 KB per CU
-    if (lds_bytes > 64 * 1024) {  // dynamic LDS above the default limit has to be allowed explicitly
-        if (gr.off64)
-            ND_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&layer_kernel<int64_t>),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize,
-                                             ND_MAX_LAYER_TRANSITS * 24));
-        else
-            ND_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&layer_kernel<int32_t>),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize,
-                                             ND_MAX_LAYER_TRANSITS * 24));
+#define ND_LAYER_LAUNCH(OFFT, W)                                                                    \
+    do {                                                                                            \
+        if (lds_bytes > 64 * 1024) /* dynamic LDS above the default limit has to be allowed */      \
+            ND_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&layer_kernel<OFFT, W>), \
+                                             hipFuncAttributeMaxDynamicSharedMemorySize,            \
+                                             ND_MAX_LAYER_TRANSITS * 24));                          \
+        hipLaunchKernelGGL((layer_kernel<OFFT, W>), dim3((unsigned)num_samples), dim3(kLayerThreads), \
+                           lds_bytes, stream, view_of<OFFT>(gr), a);                                \
+    } while (0)
+    if (gr.off64) {
+        if (a.use_weights) ND_LAYER_LAUNCH(int64_t, true);
+        else ND_LAYER_LAUNCH(int64_t, false);
+    } else {
+        if (a.use_weights) ND_LAYER_LAUNCH(int32_t, true);
+        else ND_LAYER_LAUNCH(int32_t, false);
     }
-    if (gr.off64)
-        hipLaunchKernelGGL(layer_kernel<int64_t>, dim3((unsigned)num_samples), dim3(kLayerThreads),
-                           lds_bytes, stream, view_of<int64_t>(gr), a);
-    else
-        hipLaunchKernelGGL(layer_kernel<int32_t>, dim3((unsigned)num_samples), dim3(kLayerThreads),
-                           lds_bytes, stream, view_of<int32_t>(gr), a);
+#undef ND_LAYER_LAUNCH
     ND_HIP_CHECK(hipGetLastError());
     return ND_OK;
 }

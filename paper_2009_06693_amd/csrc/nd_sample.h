@@ -84,6 +84,7 @@ struct LayerArgs {
     const int32_t* transits;      // num_samples * n_prev (roots or the previous layer)
     int32_t* out;                 // num_samples * m
     int32_t check_roots;
+    int32_t use_weights;          // entries weigh w_q(v,u) instead of c(v)
     uint32_t* status;
 };
 int layer_step(const Graph& gr, const LayerArgs& a, int64_t num_samples, hipStream_t stream);

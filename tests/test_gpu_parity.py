@@ -273,6 +273,26 @@ def test_layer_int64_and_base(small64):
     assert_steps_equal(got, [w[5:] for w in want], "layer base")
 
 
+@pytest.mark.parametrize("rps,fanout", [(64, [256, 256]), (1, [9, 200]), (300, [40, 4096])])
+def test_layer_over_edge_weights(small_w, rps, fanout):
+    dg, og = device_graph(small_w)
+    B_ = 29
+    roots = _roots(small_w, rps * B_, 14)
+    roots[::17] = -1                                       # empty transit slots
+    want = oracle.layer(og, roots, rps, fanout, seed=63, use_weights=True)
+    got, _ = gpu_sample(dg, B.ND_LAYER, roots, 63, num_steps=len(fanout), fanout=fanout,
+                        roots_per_sample=rps, use_weights=1)
+    assert_steps_equal(got, want, f"weighted layer rps={rps} fanout={fanout}")
+
+
+def test_layer_over_edge_weights_needs_weights(small):
+    dg, _ = device_graph(small)
+    p = B.nd_params_init(num_steps=1, fanout=[4], roots_per_sample=2, use_weights=1)
+    with pytest.raises(B.NdError) as e:
+        B.nd_sample_query(dg, B.ND_LAYER, p, 8)
+    assert e.value.code == B.ND_ERR_NO_WEIGHTS
+
+
 # ----------------------------------------------------------------------------- edge cases
 def test_empty_and_degenerate_inputs(small):
     dg, og = device_graph(small)

@@ -101,7 +101,8 @@ def test_random_configuration(case):
         S = max(R, S - S % R)
         roots = rng.integers(-1, g.V, S).astype(np.int32)
         fan = [int(rng.integers(1, 300)) for _ in range(int(rng.integers(1, 4)))]
-        want = [w.reshape(-1) for w in oracle.layer(og, roots, R, fan, seed, sample_id_base=base)]
+        want = [w.reshape(-1) for w in oracle.layer(og, roots, R, fan, seed, sample_id_base=base,
+                                                    use_weights=weighted)]
         got, _ = gpu_sample(dg, B.ND_LAYER, roots, seed, check_status=False, num_steps=len(fan), fanout=fan,
-                            roots_per_sample=R, sample_id_base=base)
+                            roots_per_sample=R, sample_id_base=base, use_weights=int(weighted))
     assert_steps_equal(got, want, f"random case {case} ({app})")
