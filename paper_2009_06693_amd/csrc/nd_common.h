@@ -114,7 +114,7 @@ constexpr int kSortThreads = 512;       // large inputs: 8,192 keys per tile
 constexpr int kSortItems = 16;
 constexpr int kSmallSortThreads = 256;  // small inputs: 2,048 keys per tile
 constexpr int kSmallSortItems = 8;
-constexpr int64_t kSmallSortLimit = 1 << 19;
+constexpr int64_t kSmallSortLimit = 1 << 23;
 constexpr int kMaxRadixBits = 8;
 
 struct SortPlan {
