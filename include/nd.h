@@ -217,6 +217,32 @@ int nd_sample(const nd_graph* g, int app, const nd_params* params, const int32_t
               size_t workspace_bytes, void* hip_stream);
 
 /*
+ * nd_sample for callers that cannot allocate device memory and have no
+ * workspace to bring: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same kernels and the same
+ * outputs as nd_sample, but the scratch is an array of
+ * ND_STATIC_SCRATCH_BYTES that is part of the library's code object (every GPU
+ * the library runs on holds its own copy until the process ends).  The call
+ * allocates and frees nothing, on the host side of HIP or in the library.
+ *
+ *   status_dev       device, one uint32, or NULL: receives what nd_sample_status
+ *                    would report (bit 0 set: a root was outside [0, V)), written
+ *                    by the last kernel of the call on hip_stream
+ *
+ * The graph's device must be current.  A call whose nd_sample_query
+ * workspace_bytes exceeds ND_STATIC_SCRATCH_BYTES fails with ND_ERR_TOO_LARGE
+ * before anything is launched (split the roots over several calls with
+ * sample_id_base, or use nd_sample).  All calls on one GPU share that GPU's
+ * array, which keeps the previous call's contents (the call clears what must
+ * start at zero): calls that overlap in time on one GPU, on whatever streams,
+ * race and give undefined outputs.  Other errors as nd_sample.
+ */
+#define ND_STATIC_SCRATCH_BYTES (32u << 20)
+int nd_sample_static(const nd_graph* g, int app, const nd_params* params, const int32_t* roots_dev,
+                     int64_t num_roots, uint64_t seed, int32_t* const* step_out_dev,
+                     uint32_t* status_dev, void* hip_stream);
+
+/*
  * Waits for hip_stream and reports what the last nd_sample that used this
  * workspace recorded on the device: ND_OK, or ND_ERR_BAD_ROOT.
  */

@@ -30,7 +30,7 @@ ND_ERR_NULL_POINTER, ND_ERR_BAD_ARGUMENT, ND_ERR_BAD_GRAPH, ND_ERR_BAD_WEIGHT = 
 ND_ERR_NO_WEIGHTS, ND_ERR_WORKSPACE, ND_ERR_HIP, ND_ERR_BAD_ROOT, ND_ERR_TOO_LARGE = -5, -6, -7, -8, -9
 
 EXPORTS = ["nd_params_init", "nd_graph_create", "nd_graph_destroy", "nd_graph_info", "nd_sample_query",
-           "nd_sample", "nd_sample_status", "nd_sample_stats", "nd_group_workspace_bytes",
+           "nd_sample", "nd_sample_static", "nd_sample_status", "nd_sample_stats", "nd_group_workspace_bytes",
            "nd_group_by_transit", "nd_layer_edges_workspace_bytes", "nd_layer_edges_count",
            "nd_layer_edges_fill", "nd_layer_edges_status", "nd_samples_pack", "nd_profile_enable", "nd_profile_read", "nd_last_error", "nd_version"]
 
@@ -97,6 +97,9 @@ def lib() -> ctypes.CDLL:
         L.nd_sample.restype = ctypes.c_int
         L.nd_sample.argtypes = [vp, ctypes.c_int, ctypes.POINTER(nd_params), vp, i64, u64,
                                 ctypes.POINTER(vp), vp, sz, vp]
+        L.nd_sample_static.restype = ctypes.c_int
+        L.nd_sample_static.argtypes = [vp, ctypes.c_int, ctypes.POINTER(nd_params), vp, i64, u64,
+                                       ctypes.POINTER(vp), vp, vp]
         L.nd_sample_status.restype = ctypes.c_int
         L.nd_sample_status.argtypes = [vp, vp]
         L.nd_sample_stats.restype = ctypes.c_int
@@ -237,6 +240,24 @@ def nd_sample(g: Graph, app: int, params: nd_params, roots: torch.Tensor, seed: 
     _check(lib().nd_sample(g._h, app, ctypes.byref(params), roots.data_ptr(), roots.numel(), seed, arr,
                            workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                            _stream_ptr(stream)))
+
+
+ND_STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def nd_sample_static(g: Graph, app: int, params: nd_params, roots: torch.Tensor, seed: int,
+                     step_out: Sequence[torch.Tensor], status: Optional[torch.Tensor] = None, stream=None):
+    """nd_sample on the library's own scratch array (no workspace, nothing allocated);
+    status: optional int32/uint32 CUDA tensor of one element that receives the status word."""
+    if roots.dtype != torch.int32 or not roots.is_cuda or not roots.is_contiguous():
+        raise TypeError("roots must be a contiguous int32 CUDA tensor")
+    for t in step_out:
+        if t.dtype != torch.int32 or not t.is_cuda or not t.is_contiguous():
+            raise TypeError("outputs must be contiguous int32 CUDA tensors")
+    arr = (ctypes.c_void_p * len(step_out))(*[t.data_ptr() for t in step_out])
+    _check(lib().nd_sample_static(g._h, app, ctypes.byref(params), roots.data_ptr(), roots.numel(), seed,
+                                  arr, None if status is None else status.data_ptr(),
+                                  _stream_ptr(stream)))
 
 
 def nd_sample_status(workspace: torch.Tensor, stream=None):

@@ -1,12 +1,13 @@
 // C ABI: argument checking, workspace layout and the per-step loop that the
-// host drives (Section 6 of the paper: "transit parallelism on a GPU, with
-// CPU-based coordination").  The host only enqueues kernels: every count a
-// later kernel needs (live pairs, distinct transits, class sizes) stays in
-// device memory, so nd_sample never waits for the GPU.
+// host drives (Section 6 of the paper: the host coordinates the steps, the GPU
+// executes them).  The host only enqueues kernels: every count a later kernel
+// needs (live pairs, distinct transits, class sizes) stays in device memory,
+// so nd_sample never waits for the GPU.
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "nd_common.h"
@@ -449,18 +450,22 @@ int nd_sample_query(const nd_graph* h, int app, const nd_params* params, int64_t
     return ND_OK;
 }
 
-int nd_sample(const nd_graph* h, int app, const nd_params* params, const int32_t* roots_dev,
-              int64_t num_roots, uint64_t seed, int32_t* const* step_out_dev, void* workspace_dev,
-              size_t workspace_bytes, void* hip_stream) {
-    if (!h || !params || !step_out_dev || !workspace_dev || (!roots_dev && num_roots > 0)) {
-        set_error("a required pointer is NULL");
-        return ND_ERR_NULL_POINTER;
-    }
+// The body of nd_sample and nd_sample_static.  fixed_scratch: the workspace is the library's
+// own array of a fixed size, so a call that needs more is told the limit, not a size to bring.
+static int sample_impl(const nd_graph* h, int app, const nd_params* params, const int32_t* roots_dev,
+                       int64_t num_roots, uint64_t seed, int32_t* const* step_out_dev,
+                       void* workspace_dev, size_t workspace_bytes, bool fixed_scratch,
+                       hipStream_t stream) {
     const Graph& g = *h->g;
     Plan pl;
     int rc = check_params(g, app, params, num_roots, &pl);
     if (rc != ND_OK) return rc;
     layout(&pl, g.V);
+    if (fixed_scratch && workspace_bytes < pl.total) {
+        set_error("this call needs %zu bytes of scratch; nd_sample_static has %zu (ND_STATIC_SCRATCH_BYTES): "
+                  "use fewer roots per call or nd_sample with a workspace", pl.total, workspace_bytes);
+        return ND_ERR_TOO_LARGE;
+    }
     if (workspace_bytes < pl.total || ((uintptr_t)workspace_dev % kAlign) != 0) {
         set_error("workspace needs %zu bytes aligned to %zu (got %zu)", pl.total, kAlign,
                   workspace_bytes);
@@ -474,7 +479,6 @@ int nd_sample(const nd_graph* h, int app, const nd_params* params, const int32_t
             return ND_ERR_NULL_POINTER;
         }
     }
-    hipStream_t stream = (hipStream_t)hip_stream;
     char* ws = (char*)workspace_dev;
     WsHeader* hdr = (WsHeader*)ws;
     StepCtl* ctl = (StepCtl*)(ws + pl.o_ctl);
@@ -646,6 +650,84 @@ int nd_sample(const nd_graph* h, int app, const nd_params* params, const int32_t
         }
     }
     mark_phase(ND_PHASE_NONE, stream);
+    return ND_OK;
+}
+
+int nd_sample(const nd_graph* h, int app, const nd_params* params, const int32_t* roots_dev,
+              int64_t num_roots, uint64_t seed, int32_t* const* step_out_dev, void* workspace_dev,
+              size_t workspace_bytes, void* hip_stream) {
+    if (!h || !params || !step_out_dev || !workspace_dev || (!roots_dev && num_roots > 0)) {
+        set_error("a required pointer is NULL");
+        return ND_ERR_NULL_POINTER;
+    }
+    return sample_impl(h, app, params, roots_dev, num_roots, seed, step_out_dev, workspace_dev,
+                       workspace_bytes, false, (hipStream_t)hip_stream);
+}
+
+// ---------------------------------------------------------------- scratch owned by the library
+// nd_sample_static's workspace: one array per GPU, part of the loaded code object.  In host
+// code the array's name is only a handle for hipGetSymbolAddress; its device address is looked
+// up once per device and that pointer is what kernels receive.
+static __device__ __align__(256) unsigned char nd_static_scratch[ND_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+__global__ void publish_status_kernel(const WsHeader* hdr, uint32_t* status_out) {
+    *status_out = hdr->status;
+}
+
+// Device address of the current device's copy of the array (looked up on first use).
+int static_scratch(void** out) {
+    int dev = -1;
+    ND_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) {
+        set_error("device %d is outside the %d devices nd_sample_static keeps scratch for", dev,
+                  kMaxDevices);
+        return ND_ERR_BAD_ARGUMENT;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        ND_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(nd_static_scratch)));
+        if (!p || ((uintptr_t)p % kAlign) != 0) {
+            set_error("the library's scratch array has no usable device address");
+            return ND_ERR_HIP;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return ND_OK;
+}
+}  // namespace
+
+int nd_sample_static(const nd_graph* h, int app, const nd_params* params, const int32_t* roots_dev,
+                     int64_t num_roots, uint64_t seed, int32_t* const* step_out_dev,
+                     uint32_t* status_dev, void* hip_stream) {
+    if (!h || !params || !step_out_dev || (!roots_dev && num_roots > 0)) {
+        set_error("a required pointer is NULL");
+        return ND_ERR_NULL_POINTER;
+    }
+    int dev = -1;
+    ND_HIP_CHECK(hipGetDevice(&dev));
+    if (dev != h->g->device) {
+        set_error("the graph lives on device %d but device %d is current", h->g->device, dev);
+        return ND_ERR_BAD_ARGUMENT;
+    }
+    void* scratch = nullptr;
+    int rc = static_scratch(&scratch);
+    if (rc != ND_OK) return rc;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    rc = sample_impl(h, app, params, roots_dev, num_roots, seed, step_out_dev, scratch,
+                     (size_t)ND_STATIC_SCRATCH_BYTES, true, stream);
+    if (rc != ND_OK) return rc;
+    if (status_dev) {
+        hipLaunchKernelGGL(publish_status_kernel, dim3(1), dim3(1), 0, stream, (const WsHeader*)scratch,
+                           status_dev);
+        ND_HIP_CHECK(hipGetLastError());
+    }
     return ND_OK;
 }
 
