@@ -129,18 +129,27 @@ __global__ __launch_bounds__(kLayerThreads) void layer_kernel(GraphView<OffT> g,
 
 }  // namespace
 
+// Dynamic LDS above the 64 KB default has to be allowed once per kernel; done when a graph is
+// created so that layer_step itself only launches.
+int layer_prepare() {
+#define ND_LAYER_ALLOW(OFFT, W)                                                                 \
+    ND_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&layer_kernel<OFFT, W>),     \
+                                     hipFuncAttributeMaxDynamicSharedMemorySize,                \
+                                     ND_MAX_LAYER_TRANSITS * 24))
+    ND_LAYER_ALLOW(int64_t, true);
+    ND_LAYER_ALLOW(int64_t, false);
+    ND_LAYER_ALLOW(int32_t, true);
+    ND_LAYER_ALLOW(int32_t, false);
+#undef ND_LAYER_ALLOW
+    return ND_OK;
+}
+
 int layer_step(const Graph& gr, const LayerArgs& a, int64_t num_samples, hipStream_t stream) {
     if (num_samples == 0) return ND_OK;
     const size_t lds_bytes = (size_t)a.n_prev * 24;  // at most 96 KB of the 160 KB per CU
 #define ND_LAYER_LAUNCH(OFFT, W)                                                                    \
-    do {                                                                                            \
-        if (lds_bytes > 64 * 1024) /* dynamic LDS above the default limit has to be allowed */      \
-            ND_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&layer_kernel<OFFT, W>), \
-                                             hipFuncAttributeMaxDynamicSharedMemorySize,            \
-                                             ND_MAX_LAYER_TRANSITS * 24));                          \
-        hipLaunchKernelGGL((layer_kernel<OFFT, W>), dim3((unsigned)num_samples), dim3(kLayerThreads), \
-                           lds_bytes, stream, view_of<OFFT>(gr), a);                                \
-    } while (0)
+    hipLaunchKernelGGL((layer_kernel<OFFT, W>), dim3((unsigned)num_samples), dim3(kLayerThreads),  \
+                       lds_bytes, stream, view_of<OFFT>(gr), a)
     if (gr.off64) {
         if (a.use_weights) ND_LAYER_LAUNCH(int64_t, true);
         else ND_LAYER_LAUNCH(int64_t, false);

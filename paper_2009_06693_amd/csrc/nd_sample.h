@@ -88,5 +88,7 @@ struct LayerArgs {
     uint32_t* status;
 };
 int layer_step(const Graph& gr, const LayerArgs& a, int64_t num_samples, hipStream_t stream);
+// Once per device before the first layer_step (nd_graph_create does it): lifts the kernels' LDS limit.
+int layer_prepare();
 
 }  // namespace nd

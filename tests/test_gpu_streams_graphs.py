@@ -53,6 +53,33 @@ def test_graph_replay_matches_eager(app, kw):
         torch.cuda.synchronize()
 
 
+def test_graph_replay_layer_with_large_lds():
+    """A layer step with 4,096 transit slots per sample needs 96 KB of dynamic LDS; allowing that
+    is done when the graph is created, so the call itself only launches and can be captured."""
+    g = _small
+    dg, og = device_graph(g)
+    R, fan = 64, [4096, 512]                       # step 1 has n_prev = 4,096
+    roots_np = inputs.permutation(g.V, 5)[:R * 6].copy()
+    roots = torch.as_tensor(roots_np, device="cuda:0")
+    p = B.nd_params_init(num_steps=2, fanout=fan, roots_per_sample=R)
+    s = B.Sampler(dg, B.ND_LAYER, p, roots_np.size)
+    print("[graph] capturing a layer call with n_prev = 4096", flush=True)
+    graph = torch.cuda.CUDAGraph()            # captured before any eager layer call of this shape
+    with torch.cuda.graph(graph):
+        s.run(roots, 31)
+    want = oracle.layer(og, roots_np, R, fan, 31)
+    for rep in range(3):
+        for o in s.out:
+            o.fill_(-9)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (o, w) in enumerate(zip(s.out, want)):
+            assert np.array_equal(o.cpu().numpy(), np.asarray(w).reshape(-1)), f"replay {rep}, step {i}"
+        s.run(roots, 40 + rep)
+        torch.cuda.synchronize()
+
+
 def test_two_streams_side_by_side():
     g = _small
     dg, og = device_graph(g)
