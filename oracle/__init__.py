@@ -21,8 +21,15 @@ _lib = None
 NULL = -1
 
 
-def compile_oracle(src: str, lib: str) -> None:
-    subprocess.run(["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-shared", "-fPIC", src, "-o", lib,
+SANITIZE_FLAGS = ["-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+                  "-fno-omit-frame-pointer", "-g"]
+
+
+def compile_oracle(src: str, lib: str, sanitize: bool = False) -> None:
+    """sanitize: build with AddressSanitizer and UndefinedBehaviorSanitizer (host code only; the
+    process that loads such a build needs the sanitizer runtime first in LD_PRELOAD)."""
+    opt = ["-O1", *SANITIZE_FLAGS] if sanitize else ["-O2"]
+    subprocess.run(["gcc", *opt, "-std=c11", "-Wall", "-Wextra", "-shared", "-fPIC", src, "-o", lib,
                     "-lm"], check=True)
 
 

@@ -23,15 +23,24 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "graphgen.cpp")
-_LIB = os.path.join(_HERE, "libgraphgen.so")
+# ND_GRAPHGEN_LIB lets a test point the module at a build with sanitizers
+_LIB = os.environ.get("ND_GRAPHGEN_LIB", os.path.join(_HERE, "libgraphgen.so"))
 _lib = None
+
+
+def compile_generator(lib: str, sanitize: bool = False) -> None:
+    """sanitize: AddressSanitizer + UndefinedBehaviorSanitizer build (host code only)."""
+    opt = (["-O1", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+            "-fno-omit-frame-pointer", "-g"] if sanitize else ["-O3"])
+    subprocess.run(["g++", *opt, "-std=c++17", "-fopenmp", "-shared", "-fPIC", _SRC, "-o", lib], check=True)
 
 
 def build(force: bool = False) -> str:
     """Compiles the generator (host code only) next to its source."""
+    if "ND_GRAPHGEN_LIB" in os.environ:
+        return _LIB
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["g++", "-O3", "-std=c++17", "-fopenmp", "-shared", "-fPIC", _SRC, "-o", _LIB]
-        subprocess.run(cmd, check=True)
+        compile_generator(_LIB)
     return _LIB
 
 

@@ -203,6 +203,46 @@ def test_layer_draw_is_monotone_over_the_concatenation():
     assert abs(first / len(seq) - (1 / 3) / (1 / 3 + 1 / 2)) < 0.02
 
 
+def test_layer_step_is_part_of_the_counter():
+    """Section 3, "Layer Sampling": every step draws afresh.  A chain 0 -> {1} -> {2, 3, 4}: step 0
+    can only add vertex 1, so step 1 has the single transit 1 of degree 3 and its draw j is
+    adj(1)[x // c] with x from the generator call (seed, sample, slot j, step 1)."""
+    g = inputs.from_edges(5, [(0, 1), (1, 2), (1, 3), (1, 4)])
+    seed, base, B_, m = 41, 11, 40, 9
+    out = oracle.layer(_og(g), np.zeros(B_, dtype=np.int32), 1, [1, m], seed=seed, sample_id_base=base)
+    assert (out[0] == 1).all()
+    c = (1 << 48) // 9
+    same_as_step0 = 0
+    for b in range(B_):
+        for j in range(m):
+            r = oracle.draw(seed, base + b, j, 1)
+            x = ((int(r[0]) << 32 | int(r[1])) * (3 * c)) >> 64
+            assert out[1][b, j] == 2 + x // c
+            r0 = oracle.draw(seed, base + b, j, 0)
+            x0 = ((int(r0[0]) << 32 | int(r0[1])) * (3 * c)) >> 64
+            same_as_step0 += int(out[1][b, j] == 2 + x0 // c)
+    assert same_as_step0 < 0.5 * B_ * m          # the test can tell the two calls apart
+
+
+def test_weighted_layer_step_is_part_of_the_counter():
+    """The same chain with edge weights: step 1's draw is the weighted-walk draw from vertex 1 with
+    the random words of (seed, sample, slot j, step 1)."""
+    g = inputs.from_edges(5, [(0, 1), (1, 2), (1, 3), (1, 4)], weights=[1.0, 1.0, 2.5, 4.0])
+    og = _og(g)
+    seed, base, B_, m = 43, 5, 40, 9
+    out = oracle.layer(og, np.zeros(B_, dtype=np.int32), 1, [1, m], seed=seed, sample_id_base=base,
+                       use_weights=True)
+    assert (out[0] == 1).all()
+    differs = 0
+    for b in range(B_):
+        for j in range(m):
+            r = oracle.draw(seed, base + b, j, 1)
+            assert out[1][b, j] == 2 + og.weighted_index(1, int(r[0]), int(r[1]))
+            r0 = oracle.draw(seed, base + b, j, 0)
+            differs += int(out[1][b, j] != 2 + og.weighted_index(1, int(r0[0]), int(r0[1])))
+    assert differs > 0.2 * B_ * m
+
+
 def test_layer_all_dead_transits_give_null():
     g = _layer_graph()
     out = oracle.layer(_og(g), np.array([5, -1, 5, 5], dtype=np.int32), 2, [3, 3], seed=1)
@@ -295,6 +335,21 @@ def test_unique_refill_is_uniform_over_the_remaining_neighbours():
             if cand != a:
                 assert out[s, 1] == cand
                 break
+
+
+def test_unique_sample_id_base_reproduces_a_slice():
+    """Refill draws carry the sample's global id too: a call on roots[a:b] with base a is that
+    slice of the call on all roots (small neighbourhoods, so that many slots do draw again)."""
+    g = inputs.small_graph(7, 700, seed=4)
+    og = _og(g)
+    roots = np.arange(120, dtype=np.int32) % g.V
+    full = oracle.khop(og, roots, [6, 4], seed=19, unique_rounds=5)
+    plain = oracle.khop(og, roots, [6, 4], seed=19)
+    assert (full[0] != plain[0]).any()           # the refill really ran
+    part = oracle.khop(og, roots[30:90], [6, 4], seed=19, unique_rounds=5, sample_id_base=30)
+    assert (full[0][30:90] == part[0]).all() and (full[1][30:90] == part[1]).all()
+    shifted = oracle.khop(og, roots[30:90], [6, 4], seed=19, unique_rounds=5, sample_id_base=0)
+    assert (full[0][30:90] != shifted[0]).any()
 
 
 def test_unique_exhausts_small_neighbourhoods():

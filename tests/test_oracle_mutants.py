@@ -28,6 +28,17 @@ MUTANTS = {
     "walk_does_not_advance": ("            out[(int64_t)i * S + s] = next;\n            v = next;\n        }\n    }\n    return 0;\n}\n\n/* ------------------------------------------------------------------------ */\n/* Personalised",
                               "            out[(int64_t)i * S + s] = next;\n        }\n    }\n    return 0;\n}\n\n/* ------------------------------------------------------------------------ */\n/* Personalised"),
     "ppr_coin_inverted": ("if ((uint64_t)r[3] >= thr) {", "if ((uint64_t)r[3] < thr) {"),
+    "ppr_coin_from_the_word_that_picks_the_neighbour": ("if ((uint64_t)r[3] >= thr) {", "if ((uint64_t)r[0] >= thr) {"),
+    "ppr_sample_id_base_ignored": ("draw4(seed, (uint32_t)(sample_id_base + (uint64_t)s), 0u, (uint32_t)i, 0u, r);\n                if ((uint64_t)r[3] >= thr) {",
+                                   "draw4(seed, (uint32_t)s, 0u, (uint32_t)i, 0u, r);\n                if ((uint64_t)r[3] >= thr) {"),
+    "n2v_sample_id_base_ignored": ("const uint32_t sid = (uint32_t)(sample_id_base + (uint64_t)s);\n        int32_t t = NDO_NULL;",
+                                   "const uint32_t sid = (uint32_t)s;\n        int32_t t = NDO_NULL;"),
+    "unique_refill_sample_id_base_ignored": ("draw4(seed, (uint32_t)(sample_id_base + (uint64_t)s), (uint32_t)j, (uint32_t)i,\n                          (uint32_t)r, rn);",
+                                             "draw4(seed, (uint32_t)(r == 0 ? sample_id_base + (uint64_t)s : (uint64_t)s), (uint32_t)j, (uint32_t)i,\n                          (uint32_t)r, rn);"),
+    "layer_step_dropped_from_the_counter": ("draw4(seed, (uint32_t)(sample_id_base + (uint64_t)b), (uint32_t)j, (uint32_t)i, 0u, r);\n                    const uint64_t x = ndo_mulhi64(((uint64_t)r[0] << 32) | r[1], total);\n                    uint64_t before = 0; /* mass of the lists in front of the current one */",
+                                            "draw4(seed, (uint32_t)(sample_id_base + (uint64_t)b), (uint32_t)j, 0u, 0u, r);\n                    const uint64_t x = ndo_mulhi64(((uint64_t)r[0] << 32) | r[1], total);\n                    uint64_t before = 0; /* mass of the lists in front of the current one */"),
+    "weighted_layer_step_dropped_from_the_counter": ("draw4(seed, (uint32_t)(sample_id_base + (uint64_t)b), (uint32_t)j, (uint32_t)i, 0u, r);\n                    const uint64_t x = ndo_mulhi64(((uint64_t)r[0] << 32) | r[1], total);\n                    uint64_t before = 0; /* weight of the lists in front of the current one */",
+                                                     "draw4(seed, (uint32_t)(sample_id_base + (uint64_t)b), (uint32_t)j, 0u, 0u, r);\n                    const uint64_t x = ndo_mulhi64(((uint64_t)r[0] << 32) | r[1], total);\n                    uint64_t before = 0; /* weight of the lists in front of the current one */"),
     "n2v_common_and_far_swapped": ("else if (has_edge(g, t, u)) bias = b_com;\n    else bias = b_far;",
                                    "else if (has_edge(g, t, u)) bias = b_far;\n    else bias = b_com;"),
     "n2v_return_case_dropped": ("else if (u == t) bias = b_ret;", "else if (0) bias = b_ret;"),

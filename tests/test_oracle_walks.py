@@ -154,6 +154,45 @@ def test_ppr_length_is_truncated_geometric():
     assert stats.chisquare(counts, pmf * S).pvalue > 1e-4
 
 
+def test_ppr_coin_is_its_own_word_and_leaves_the_draw_uniform():
+    """Section 3, "Random walks": the walk ends with a given probability, whatever it would have
+    drawn.  The coin is word R3 of the step's generator call; the neighbour index comes from R0.
+    From the centre of a star: a walk survives step 0 exactly when R3 of the call
+    (seed, sample, slot 0, step 0) reaches the threshold, and among the survivors the chosen leaf
+    is still uniform (a coin taken from the word that also picks the neighbour would empty the
+    low-index leaves)."""
+    leaves = 10
+    edges = [(0, i) for i in range(1, leaves + 1)] + [(i, 0) for i in range(1, leaves + 1)]
+    g = inputs.from_edges(leaves + 1, edges)
+    prob, S, seed, base = 0.3, 40000, 23, 7
+    thr = int(np.floor(prob * 2.0 ** 32))
+    out = oracle.ppr(_og(g), np.zeros(S, dtype=np.int32), 2, prob, seed=seed, sample_id_base=base)
+    for s in range(300):
+        r = oracle.draw(seed, base + s, 0, 0)
+        assert (out[0, s] >= 0) == (int(r[3]) >= thr)
+        if out[0, s] >= 0:
+            assert out[0, s] == 1 + (int(r[0]) * leaves >> 32)
+            r1 = oracle.draw(seed, base + s, 0, 1)               # step 1: from the leaf back to 0
+            assert (out[1, s] >= 0) == (int(r1[3]) >= thr)
+    alive = out[0] >= 0
+    assert abs(alive.mean() - (1 - thr / 2.0 ** 32)) < 0.01
+    counts = np.bincount(out[0][alive], minlength=leaves + 1)[1:]
+    assert counts.min() > 0
+    assert stats.chisquare(counts).pvalue > 1e-4
+
+
+def test_ppr_sample_id_base_reproduces_a_slice():
+    g = _six_vertex_graph(True)
+    og = _og(g)
+    roots = np.arange(900, dtype=np.int32) % 6
+    for weighted in (False, True):
+        full = oracle.ppr(og, roots, 12, 0.15, seed=9, use_weights=weighted)
+        part = oracle.ppr(og, roots[200:420], 12, 0.15, seed=9, use_weights=weighted, sample_id_base=200)
+        assert (full[:, 200:420] == part).all()
+        shifted = oracle.ppr(og, roots[200:420], 12, 0.15, seed=9, use_weights=weighted, sample_id_base=0)
+        assert (full[:, 200:420] != shifted).any()
+
+
 def test_ppr_certain_termination():
     g = _six_vertex_graph()
     out = oracle.ppr(_og(g), np.arange(6), 5, 1.0, seed=1)
@@ -233,6 +272,19 @@ def test_node2vec_with_unit_biases_is_uniform_deepwalk():
     a = oracle.deepwalk(og, roots, 20, seed=9)
     b = oracle.node2vec(og, roots, 20, 1.0, 1.0, seed=9)
     assert (a == b).all()
+
+
+def test_node2vec_sample_id_base_reproduces_a_slice():
+    g = _n2v_graph(True)
+    og = _og(g)
+    roots = np.arange(700, dtype=np.int32) % g.V
+    for weighted, attempts in ((False, 64), (True, 64), (True, 0)):
+        kw = dict(p=2.0, q=0.5, seed=14, use_weights=weighted, max_attempts=attempts)
+        full = oracle.node2vec(og, roots, 9, **kw)
+        part = oracle.node2vec(og, roots[150:380], 9, sample_id_base=150, **kw)
+        assert (full[:, 150:380] == part).all()
+        shifted = oracle.node2vec(og, roots[150:380], 9, sample_id_base=0, **kw)
+        assert (full[:, 150:380] != shifted).any()
 
 
 def test_node2vec_rejects_bad_parameters():
