@@ -1,10 +1,17 @@
 """GPU parity at the full sizes of the five workloads, in the launch
 configuration bench.py times (one nd_sample call over every root,
-transit-parallel, default scheduling).  The two small workloads are compared
-with the oracle in full; for the three large ones the oracle computes windows
-of consecutive samples one by one (a sample's output depends only on its own
-id, root and the seed), and properties that hold at any size are checked on
-the whole output."""
+transit-parallel, default scheduling).  All five workloads are compared with
+the oracle in full, every element of every step: for the three large ones the
+unchanged single-threaded oracle runs over disjoint ranges of samples on the
+host's threads (a sample's output depends only on its own id, root and the
+seed), and one range is computed a second time on the calling thread alone and
+must give the same values.  Windows of samples remain only where a full oracle
+run would take minutes: the 2.1 G-slot k-hop call at the ABI's size limit, the
+unique-neighbour k-hop (whose oracle is quadratic in the slots of a sample),
+the multi-dimensional walk and the recorded edges."""
+import concurrent.futures
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -29,6 +36,25 @@ def _run(dg, app, roots_np, seed, **kw):
     torch.cuda.synchronize()
     s.status()
     return s, out
+
+
+def _oracle_over_ranges(fn, n_samples, chunk, compare):
+    """fn(a, b) -> oracle output for samples [a, b); compare(a, b, want) checks it against the GPU
+    output.  The chunks run on the host's threads (the oracle's C calls release the interpreter
+    lock); comparing happens on the calling thread, in order.  The first chunk is computed once
+    more without the pool and must be identical."""
+    threads = max(1, min(16, os.cpu_count() or 1))
+    ranges = [(a, min(n_samples, a + chunk)) for a in range(0, n_samples, chunk)]
+    print(f"[config] oracle over {len(ranges)} ranges of {chunk} samples on {threads} threads", flush=True)
+    first = None
+    with concurrent.futures.ThreadPoolExecutor(threads) as pool:
+        for (a, b), want in zip(ranges, pool.map(lambda r: fn(*r), ranges)):
+            if first is None:
+                first = want
+            compare(a, b, want)
+    alone = fn(*ranges[0])
+    for x, y in zip(first, alone):
+        assert np.array_equal(np.asarray(x), np.asarray(y)), "threaded and single-threaded oracle differ"
 
 
 def _windows(n, width, count, seed):
@@ -75,6 +101,24 @@ def _check_khop_windows(g, og, out, fanout, seed, windows):
             assert np.array_equal(got, want[i].reshape(-1)), f"k-hop step {i}, samples [{a},{b})"
 
 
+def _compare_khop_everywhere(og, out, n_roots, fanout, seed, chunk):
+    """Every element of every step of a k-hop call whose roots are 0 .. n_roots - 1."""
+    W = [int(x) for x in np.cumprod(fanout)]
+
+    def want(a, b):
+        return oracle.khop(og, np.arange(a, b, dtype=np.int32), fanout, seed=seed, sample_id_base=a)
+
+    def compare(a, b, w):
+        for i in range(len(fanout)):
+            got = out[i][a * W[i]:b * W[i]].cpu().numpy()
+            if not np.array_equal(got, w[i].reshape(-1)):
+                bad = np.flatnonzero(got != w[i].reshape(-1))
+                raise AssertionError(f"k-hop step {i}, samples [{a},{b}): {bad.size} entries differ, first at "
+                                     f"{a * W[i] + bad[0]}: gpu {got[bad[0]]} oracle {w[i].reshape(-1)[bad[0]]}")
+
+    _oracle_over_ranges(want, n_roots, chunk, compare)
+
+
 def _khop_properties(g, roots_t, out, fanout):
     """NULL exactly where the parent is NULL or has no out-edge; everything else is a vertex."""
     off = torch.as_tensor(g.row_offsets.astype(np.int64), device="cuda:0")
@@ -96,9 +140,7 @@ def test_config3_khop_all_roots():
     og = oracle.OracleGraph(g.row_offsets, g.col_indices)
     roots = inputs.all_vertices_roots(g)
     s, out = _run(dg, B.ND_KHOP, roots, 3, num_steps=2, fanout=[25, 10])
-    # windows of whole 1,024-root batches and one ragged last batch (233,000 = 227 * 1,024 + 552)
-    wins = [(0, 1024), (113 * 1024, 114 * 1024), (227 * 1024, g.V)]
-    _check_khop_windows(g, og, out, [25, 10], 3, wins)
+    _compare_khop_everywhere(og, out, g.V, [25, 10], 3, chunk=4096)
     _khop_properties(g, torch.as_tensor(roots, device="cuda:0"), out, [25, 10])
     # a single batch run on its own reproduces its slice of the all-at-once call
     _, one = _run(dg, B.ND_KHOP, roots[5 * 1024:6 * 1024], 3, num_steps=2, fanout=[25, 10],
@@ -117,11 +159,15 @@ def test_config4_layer():
     nb = 4096
     roots = inputs.permutation(g.V, 4)[:nb * 64].copy()
     s, out = _run(dg, B.ND_LAYER, roots, 4, num_steps=2, fanout=[2048, 2048], roots_per_sample=64)
-    for b in (0, 1, 777, 2048, 4095):
-        want = oracle.layer(og, roots[b * 64:(b + 1) * 64], 64, [2048, 2048], seed=4, sample_id_base=b)
+    def want(a, b):
+        return oracle.layer(og, roots[a * 64:b * 64], 64, [2048, 2048], seed=4, sample_id_base=a)
+
+    def compare(a, b, w):
         for i in range(2):
-            got = out[i][b * 2048:(b + 1) * 2048].cpu().numpy()
-            assert np.array_equal(got, want[i].reshape(-1)), f"layer step {i} batch {b}"
+            got = out[i][a * 2048:b * 2048].cpu().numpy()
+            assert np.array_equal(got, w[i].reshape(-1)), f"layer step {i}, batches [{a},{b})"
+
+    _oracle_over_ranges(want, nb, 32, compare)
     assert int(out[0].min()) >= 0 and int(out[1].max()) < g.V
 
 
@@ -166,7 +212,7 @@ def test_config5_khop_and_deepwalk():
     roots = inputs.all_vertices_roots(g)
     roots_t = torch.as_tensor(roots, device="cuda:0")
     s, out = _run(dg, B.ND_KHOP, roots, 5, num_steps=2, fanout=[25, 10])
-    _check_khop_windows(g, og, out, [25, 10], 5, _windows(g.V, 512, 6, 55))
+    _compare_khop_everywhere(og, out, g.V, [25, 10], 5, chunk=32768)
     _khop_properties(g, roots_t, out, [25, 10])
     stats = s.stats()
     assert stats[0, 0] == g.V and stats[1, 0] == int((out[0] >= 0).sum())
@@ -178,10 +224,19 @@ def test_config5_khop_and_deepwalk():
     del s, out, s2, out2
     torch.cuda.empty_cache()
     s, out = _run(dg, B.ND_DEEPWALK, roots, 5, num_steps=100)
-    for a, b in _windows(g.V, 2048, 4, 56):
-        want = oracle.deepwalk(og, roots[a:b], 100, seed=5, sample_id_base=a)
-        for i in range(100):
-            assert np.array_equal(out[i][a:b].cpu().numpy(), want[i]), f"walk step {i} window {a}"
+    steps = torch.stack(list(out))                      # [100, V]: one copy per range below
+
+    def want_walk(a, b):
+        return [oracle.deepwalk(og, roots[a:b], 100, seed=5, sample_id_base=a)]
+
+    def compare_walk(a, b, w):
+        got = steps[:, a:b].cpu().numpy()
+        if not np.array_equal(got, w[0]):
+            i, j = np.argwhere(got != w[0])[0]
+            raise AssertionError(f"walk {a + j} step {i}: gpu {got[i, j]} oracle {w[0][i, j]}")
+
+    _oracle_over_ranges(want_walk, g.V, 65536, compare_walk)
+    del steps
     # a walk that is alive at step i was alive at step i-1
     alive = out[0] >= 0
     for i in range(1, 100):
