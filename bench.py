@@ -2,10 +2,12 @@
 """Benchmark of the transit-parallel sampling path on one MI355X.
 
 A "step" is one pass of the whole hot path over one batch of synthetic input:
-one nd_sample call (transit enumeration, radix sort by transit, segmented scan,
-classification, the three class kernels, output compaction) over every root of
-the workload.  Inputs are resident in HBM before the timed region.  Prints one
-JSON line.
+one nd_sample call (transit enumeration, grouping by transit, scheduling
+classes, the sampling kernels, output compaction) over every root of the
+workload.  Inputs are resident in HBM before the timed region.  Prints one JSON
+line.  Without --workload the line is for the largest k-hop workload (c5_khop)
+and carries, under "also", the same measurements for the largest random-walk
+workload (c5_deepwalk), both timed in this one run.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--mode tp|sp]
 """
@@ -22,14 +24,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# Arithmetic view of a draw, for context: one Philox4x32-10 call is 20 widening 32x32->64
-# multiplies and 40 XORs.  A generator-only kernel (Philox + index, no memory) reaches about
-# 8e11 draws/s on this chip, so the generator alone caps a draw-per-lane kernel there.
-PHILOX_ONLY_DRAWS_PER_S = 8.0e11
 
-# HBM bytes per launch of the dominant kernel from two rocprofv3 --pmc runs (FETCH_SIZE, then
-# WRITE_SIZE; scaled by the factors a 1 GiB copy kernel gives: x2.0 and x1.0), averaged over the
-# launches of one call.  Source: profiles/c5_khop_tp_rocprofv3.md.  None where not profiled.
+# HBM bytes per launch of the dominant kernel from two rocprofv3 --pmc runs of this file
+# (FETCH_SIZE, then WRITE_SIZE; scaled by the factors the copy kernel of `--workload copy_calib`
+# gives: x2.0 and x1.0), averaged over the launches of one call.  Sources: the counter tables in
+# profiles/c5_khop_tp_rocprofv3.md and profiles/c5_deepwalk_tp_rocprofv3.md.  None where not profiled.
 MEASURED_TRAFFIC_BYTES = {
     ("c5_khop", "tp", "sample_sub"): int((281.4 + 2313.6 + 402.9 + 2918.0) / 2 * 1048576),
 }
@@ -125,59 +124,58 @@ def bench_layer_edges(args, B, inputs, torch, np):
                               "edges_fill": round(t_fill / k, 4)}}))
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c5_khop", choices=sorted(WORKLOADS) + ["copy_calib", "c4_layer_edges"])
-    ap.add_argument("--mode", default="tp", choices=["tp", "sp"])
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seconds", type=float, default=12.0)
-    ap.add_argument("--sub-max", type=int, default=0)
-    ap.add_argument("--wg-max", type=int, default=0)
-    ap.add_argument("--group-bits", type=int, default=0,
-                    help="0: exact transit grouping (default); b: group by the top b bits of the vertex id only")
-    ap.add_argument("--force-class", type=int, default=-1,
-                    help="ablation: -1 balanced (default), 0/1/2 every transit sub-wavefront/workgroup/grid")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU only; sampling shards by samples with the "
-              "graph replicated, which one GPU cannot show (use --gpus 1)", file=sys.stderr)
-        sys.exit(2)
+def measure_copy_gbps(torch, steps=5):
+    """Device-to-device copy of 1 GiB on the current stream: the box's copy bandwidth
+    (bytes read + bytes written per second)."""
+    n = 1 << 28
+    src = torch.arange(n, dtype=torch.int32, device="cuda:0")
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    del src, dst
+    torch.cuda.empty_cache()
+    return n * 4, ms, 2 * n * 4 / (ms * 1e-3) / 1e9
 
-    import numpy as np
-    import torch
-    from paper_2009_06693_amd import binding as B
-    from paper_2009_06693_amd import inputs
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    if args.workload == "copy_calib":
-        # A plain device-to-device copy of known size: the yardstick that turns the
-        # FETCH_SIZE / WRITE_SIZE counters of a profiler run into bytes.
-        n = 1 << 28                                  # 2^28 int32 = 1 GiB read + 1 GiB written
-        src = torch.arange(n, dtype=torch.int32, device="cuda:0")
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(args.steps):
-            dst.copy_(src)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / args.steps
-        print(json.dumps({"workload": "copy_calib", "bytes_read": n * 4, "bytes_written": n * 4,
-                          "ms_per_copy": round(ms, 4),
-                          "copy_GBps": round(2 * n * 4 / (ms * 1e-3) / 1e9, 1)}))
-        return
-    if args.workload == "c4_layer_edges":
-        return bench_layer_edges(args, B, inputs, torch, np)
-    builder, app_name, pkw, desc = WORKLOADS[args.workload]
+def run_oracle(oracle, og, app, B, pkw, roots_np, seed, n, first=0):
+    """The oracle on roots[first : first + n]; `first` is a multiple of the sample size.
+    Returns (non-NULL entries, seconds, per-step arrays)."""
+    r = roots_np[first:first + n]
+    base = first // pkw.get("roots_per_sample", 1)
+    w = bool(pkw.get("use_weights", 0))
+    t = time.perf_counter()
+    if app == B.ND_KHOP:
+        o = oracle.khop(og, r, pkw["fanout"], seed, sample_id_base=base, unique_rounds=pkw.get("unique_rounds", 0))
+    elif app == B.ND_DEEPWALK:
+        o = list(oracle.deepwalk(og, r, pkw["num_steps"], seed, use_weights=w, sample_id_base=base))
+    elif app == B.ND_PPR:
+        o = list(oracle.ppr(og, r, pkw["num_steps"], pkw["term_prob"], seed, use_weights=w, sample_id_base=base))
+    elif app == B.ND_MULTIRW:
+        o = list(oracle.multirw(og, r, pkw["roots_per_sample"], pkw["num_steps"], seed, sample_id_base=base))
+    elif app == B.ND_NODE2VEC:
+        o = list(oracle.node2vec(og, r, pkw["num_steps"], pkw["p"], pkw["q"], seed, use_weights=w,
+                                 sample_id_base=base))
+    else:
+        o = oracle.layer(og, r, pkw["roots_per_sample"], pkw["fanout"], seed, sample_id_base=base, use_weights=w)
+    dt = time.perf_counter() - t
+    return sum(int((x >= 0).sum()) for x in o), dt, o
+
+
+def run_workload(name, args, B, inputs, torch, np, cpu_baseline):
+    """Times K nd_sample calls of one workload; returns the result fields of the JSON line."""
+    builder, app_name, pkw, desc = WORKLOADS[name]
     app = {"deepwalk": B.ND_DEEPWALK, "ppr": B.ND_PPR, "node2vec": B.ND_NODE2VEC, "khop": B.ND_KHOP,
            "layer": B.ND_LAYER, "multirw": B.ND_MULTIRW}[app_name]
     t0 = time.time()
     g = getattr(inputs, builder)()
-    if args.workload == "c4_layer_symmetric":
+    if name == "c4_layer_symmetric":
         deg = np.diff(g.row_offsets).astype(np.float64)
         src = np.repeat(np.arange(g.V), np.diff(g.row_offsets))
         g.weights = (16384.0 / (deg[src] * deg[g.col_indices])).astype(np.float32)
@@ -192,8 +190,9 @@ def main():
         roots_np = np.arange(g.V, dtype=np.int32)
     roots = torch.as_tensor(roots_np, device="cuda:0")
     mode = B.ND_MODE_TRANSIT_PARALLEL if args.mode == "tp" else B.ND_MODE_SAMPLE_PARALLEL
-    p = B.nd_params_init(mode=mode, sched_sub_max=args.sub_max, sched_wg_max=args.wg_max, sched_group_bits=args.group_bits,
-                         sched_force_class=args.force_class, **pkw)
+    p = B.nd_params_init(mode=mode, sched_sub_max=args.sub_max, sched_wg_max=args.wg_max,
+                         sched_group_bits=args.group_bits, sched_force_class=args.force_class,
+                         sched_window=args.window, **pkw)
     s = B.Sampler(dg, app, p, int(roots.numel()))
     seed = 1
 
@@ -203,8 +202,8 @@ def main():
     s.status()
 
     # Timed region: K whole nd_sample calls, bracketed by events on the launch stream.
-    # Phase marks (HIP events inside the library) give the per-kernel durations of the
-    # same region.
+    # Phase marks (HIP events inside the library, same stream) give the per-kernel durations
+    # of the same region.
     B.nd_profile_enable(True)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
@@ -222,139 +221,206 @@ def main():
     B.nd_profile_enable(False)
     ms_per_step = ms_total / args.steps
 
+    n_steps = len(s.step_len)
     slots = int(sum(s.step_len))
-    live = int(sum(int((o >= 0).sum()) for o in out))
+    live_per_step = [int((o >= 0).sum()) for o in out]
+    live = int(sum(live_per_step))
     value = live / (ms_per_step * 1e-3)
 
-    # ---- roofline of the dominant kernel (the phase with the largest share that is one launch)
+    # ---- roofline of the dominant kernel: the kernel phase with the largest share of the call
     stats = s.stats() if (mode == B.ND_MODE_TRANSIT_PARALLEL and app != B.ND_LAYER) else None
     phase_ms = {k: v[0] / args.steps for k, v in phases.items() if v[1] > 0}
     launches = {k: v[1] / args.steps for k, v in phases.items() if v[1] > 0}
-    kernel_phases = [k for k in ("sample_sub", "sample_sp", "layer", "sample_wg") if k in phase_ms]
+    kernel_phases = [k for k in ("sample_sub", "walk_window", "sample_sp", "layer", "sample_wg") if k in phase_ms]
     dom = max(kernel_phases, key=lambda k: phase_ms[k])
     avg_launch_ms = phase_ms[dom] / launches[dom]
-    if stats is not None and dom == "sample_sub":
-        # draws made by the step's sampling kernel: those of all live pairs
-        m_per_step = [pkw.get("fanout", [1] * len(s.step_len))[i] if app == B.ND_KHOP else 1
-                      for i in range(len(s.step_len))]
-        draws = sum(int(stats[i, 0]) * m_per_step[i] for i in range(len(s.step_len)))
-    else:
-        draws = live if dom != "sample_sp" else slots
-    draws_per_launch = draws / launches[dom]
-    # Algorithmic bytes the dominant kernel must move.  Transit-parallel: per draw 4 (one
-    # adjacency entry) + 4 (one output entry); per pair 8 (sorted transit and slot) + two row
-    # offsets, shared by the pair's m draws.  Sample-parallel: 4 per output entry, 4 per live
-    # one (adjacency), and per parent slot 4 (the transit) + two row offsets if it is live.
-    # Layer: per sample and transit slot 4 + two row offsets, per draw 4 + 4.
-    off_bytes = 16.0 if g.row_offsets.dtype.itemsize == 8 else 8.0
-    if dom == "sample_sp":
+    off_bytes = 16.0 if g.row_offsets.dtype.itemsize == 8 else 8.0        # the two row offsets of a transit
+    m_per_step = [pkw["fanout"][i] if app == B.ND_KHOP else 1 for i in range(n_steps)]
+    mean_deg = max(2.0, g.E / max(1, g.V))
+    log_deg = float(np.ceil(np.log2(mean_deg)))
+    # Algorithmic bytes of one call of the dominant kernel (what the method itself must move; an
+    # adjacency entry counts 4 bytes, not the cache line it arrives in):
+    #   transit-parallel, GPU-wide grouping (sample_tp_kernel): per live pair 8 (sorted transit and
+    #     slot), per distinct transit the two row offsets, per non-NULL draw 4 (adjacency entry),
+    #     per draw 4 (output entry).  NULL children of dead slots are written by the sort's first pass.
+    #   walks grouped per window (walk_window_kernel): the pairs stay in LDS; per step and distinct
+    #     transit of a window the two row offsets, per non-NULL draw 4, per sample 4 (output entry,
+    #     NULL included); once per call 4 per root.  Weighted draws add 8 bytes per probe of the running
+    #     sums (log2 of the mean degree probes), node2vec 4 + 4 log2(mean degree) per membership test.
+    #   sample-parallel: per output entry 4, per non-NULL one 4, per parent slot 4 + (if live) two offsets.
+    #   layer: per sample and transit slot 4 + two row offsets, per draw 4 + 4.
+    if dom in ("sample_sub", "sample_wg") and stats is not None:
+        draws = sum(int(stats[i, 0]) * m_per_step[i] for i in range(n_steps))
+        total_bytes = sum(8.0 * int(stats[i, 0]) + off_bytes * int(stats[i, 1]) + 4.0 * live_per_step[i]
+                          + 4.0 * int(stats[i, 0]) * m_per_step[i] for i in range(n_steps))
+    elif dom == "walk_window" and stats is not None:
+        draws = sum(int(stats[i, 0]) for i in range(n_steps))
+        per_draw = 4.0
+        if pkw.get("use_weights", 0) and app != B.ND_NODE2VEC:
+            per_draw += 8.0 * log_deg
+        if app == B.ND_NODE2VEC:
+            per_draw += 4.0 + 4.0 * log_deg
+        total_bytes = sum(off_bytes * int(stats[i, 1]) + per_draw * live_per_step[i] + 4.0 * s.step_len[i]
+                          for i in range(n_steps)) + 4.0 * int(roots.numel())
+        if app == B.ND_MULTIRW:                       # the picked root is read and replaced in the root sets
+            total_bytes += 8.0 * draws
+    elif dom == "sample_sp":
+        draws = slots
         parents = [int(roots.numel())] + [int(x) for x in s.step_len[:-1]]
-        live_parents = [int((roots >= 0).sum())] + [int((o >= 0).sum()) for o in out[:-1]]
+        live_parents = [int((roots >= 0).sum())] + live_per_step[:-1]
         total_bytes = 4.0 * slots + 4.0 * live + 4.0 * sum(parents) + off_bytes * sum(live_parents)
-        hbm_bytes_per_draw = total_bytes / max(1, draws)
-    elif dom == "layer":
+    else:  # layer
+        draws = live
         rps = pkw["roots_per_sample"]
         n_samples = int(roots.numel()) // rps
         n_prev = [rps] + list(pkw["fanout"][:-1])
         total_bytes = n_samples * sum(n * (4.0 + off_bytes) for n in n_prev) + 8.0 * live
-        hbm_bytes_per_draw = total_bytes / max(1, draws)
-    else:
-        m_avg = draws / max(1, sum(int(stats[i, 0]) for i in range(len(s.step_len)))) if stats is not None else 1.0
-        hbm_bytes_per_draw = 8.0 + (8.0 + off_bytes) / max(m_avg, 1.0)
-    hbm_gbs = draws_per_launch * hbm_bytes_per_draw / (avg_launch_ms * 1e-3) / 1e9
-    draws_per_s = draws_per_launch / (avg_launch_ms * 1e-3)
+    alg_per_launch = total_bytes / launches[dom]
+    hbm_gbs = alg_per_launch / (avg_launch_ms * 1e-3) / 1e9
+    traffic = MEASURED_TRAFFIC_BYTES.get((name, args.mode, dom))
     roofline = {
-        "kernel": {"sample_sub": "sample_tp_kernel", "sample_sp": "sample_sp_kernel",
-                   "layer": "layer_kernel", "sample_wg": "sample_tp_kernel"}[dom],
+        "kernel": {"sample_sub": "sample_tp_kernel", "sample_sp": "sample_sp_kernel", "layer": "layer_kernel",
+                   "sample_wg": "sample_tp_kernel", "walk_window": "walk_window_kernel"}[dom],
         "bound": "hbm", "achieved": round(hbm_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(hbm_gbs / HBM_PEAK_GBS, 4),
-        "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, args.mode, dom)),
-        "algorithmic_bytes_per_launch": int(draws_per_launch * hbm_bytes_per_draw),
-        "algorithmic_bytes_per_draw": round(hbm_bytes_per_draw, 2),
+        "traffic": traffic,
+        "counter_frac": None if traffic is None else round(traffic / (avg_launch_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "overfetch": None if traffic is None else round(traffic / alg_per_launch, 3),
+        "algorithmic_bytes_per_launch": int(alg_per_launch),
+        "algorithmic_bytes_per_draw": round(total_bytes / max(1, draws), 2),
         "avg_launch_ms": round(avg_launch_ms, 4), "launches_per_step": launches[dom],
-        "draws_per_launch": int(draws_per_launch),
-        "alu_view": {"draws_per_s": round(draws_per_s, 1),
-                     "generator_only_draws_per_s": PHILOX_ONLY_DRAWS_PER_S,
-                     "frac": round(draws_per_s / PHILOX_ONLY_DRAWS_PER_S, 4)},
+        "draws_per_launch": int(draws / launches[dom]),
     }
 
-    cpu_baseline = None
-    if not args.no_cpu_baseline:
-        import oracle
-        og = oracle.OracleGraph(g.row_offsets, g.col_indices, g.weights)
-
-        def run_oracle(n, first=0):
-            """The oracle on roots[first : first + n]; `first` is a multiple of the sample size."""
-            r = roots_np[first:first + n]
-            base = first // pkw.get("roots_per_sample", 1)
-            w = bool(pkw.get("use_weights", 0))
-            t = time.perf_counter()
-            if app == B.ND_KHOP:
-                o = oracle.khop(og, r, pkw["fanout"], seed, sample_id_base=base,
-                                unique_rounds=pkw.get("unique_rounds", 0))
-            elif app == B.ND_DEEPWALK:
-                o = list(oracle.deepwalk(og, r, pkw["num_steps"], seed, use_weights=w, sample_id_base=base))
-            elif app == B.ND_PPR:
-                o = list(oracle.ppr(og, r, pkw["num_steps"], pkw["term_prob"], seed, use_weights=w,
-                                    sample_id_base=base))
-            elif app == B.ND_MULTIRW:
-                o = list(oracle.multirw(og, r, pkw["roots_per_sample"], pkw["num_steps"], seed,
-                                        sample_id_base=base))
-            elif app == B.ND_NODE2VEC:
-                o = list(oracle.node2vec(og, r, pkw["num_steps"], pkw["p"], pkw["q"], seed, use_weights=w,
-                                         sample_id_base=base))
-            else:
-                o = oracle.layer(og, r, pkw["roots_per_sample"], pkw["fanout"], seed, sample_id_base=base,
-                                 use_weights=w)
-            dt = time.perf_counter() - t
-            return sum(int((x >= 0).sum()) for x in o), dt, o
-
-        unit = pkw.get("roots_per_sample", 1)
-        n_probe = min(int(roots_np.size), 2048 * unit if app != B.ND_LAYER else 2 * unit)
-        live_probe, dt_probe, o_probe = run_oracle(n_probe)
-        # the probe doubles as a parity spot-check of this very run
-        for i, x in enumerate(o_probe):
-            got = out[i][: x.size].cpu().numpy()
-            assert np.array_equal(got, np.asarray(x).reshape(-1)), f"GPU and oracle differ at step {i}"
+    # ---- the oracle on a prefix of the same roots: a parity check of this very run, and the CPU baseline
+    import oracle
+    og = oracle.OracleGraph(g.row_offsets, g.col_indices, g.weights)
+    unit = pkw.get("roots_per_sample", 1)
+    n_probe = min(int(roots_np.size), 2048 * unit if app != B.ND_LAYER else 2 * unit)
+    live_probe, dt_probe, o_probe = run_oracle(oracle, og, app, B, pkw, roots_np, seed, n_probe)
+    for i, x in enumerate(o_probe):
+        got = out[i][: x.size].cpu().numpy()
+        assert np.array_equal(got, np.asarray(x).reshape(-1)), f"{name}: GPU and oracle differ at step {i}"
+    parity_probe = f"first {n_probe} roots, every step, equal to the oracle"
+    baseline = None
+    if cpu_baseline:
         n = int(min(roots_np.size, max(n_probe, n_probe * args.cpu_seconds / max(dt_probe, 1e-6))))
         n -= n % unit
-        live_cpu, dt_cpu, _ = run_oracle(n)
-        cpu_baseline = {"value": round(live_cpu / dt_cpu, 1), "unit": "sampled vertices/s", "cores": 1,
-                        "kind": "oracle",
-                        "sample": f"first {n} of {roots_np.size} roots of the same workload, "
-                                  f"{dt_cpu:.1f} s of single-threaded oracle time"}
-        # The same oracle, unchanged, on disjoint ranges of roots from several host threads (samples
-        # are independent; the C calls release the interpreter lock).
+        live_cpu, dt_cpu, o_single = run_oracle(oracle, og, app, B, pkw, roots_np, seed, n)
+        for i, x in enumerate(o_single):     # the whole single-threaded sample against this run's GPU output
+            x = np.asarray(x)
+            got = out[i][: x.size].cpu().numpy()
+            assert np.array_equal(got, x.reshape(-1)), f"{name}: GPU and oracle differ at step {i} (baseline sample)"
+        parity_probe = f"first {n} roots, every step, equal to the oracle"
+        baseline = {"value": round(live_cpu / dt_cpu, 1), "unit": "sampled vertices/s", "cores": 1,
+                    "kind": "oracle",
+                    "sample": f"first {n} of {roots_np.size} roots of the same workload, "
+                              f"{dt_cpu:.1f} s of single-threaded oracle time"}
+        # The same oracle, unchanged, on disjoint ranges of the same sample from several host threads
+        # (samples are independent; the C calls release the interpreter lock).  Its output must be
+        # the single-threaded one.
         import concurrent.futures
         threads = max(1, min(16, os.cpu_count() or 1))
-        per = (min(n, int(roots_np.size) // threads) // unit) * unit
+        per = (n // threads // unit) * unit
         if threads > 1 and per > 0:
             t = time.perf_counter()
             with concurrent.futures.ThreadPoolExecutor(threads) as pool:
-                parts = list(pool.map(lambda k: run_oracle(per, k * per)[0], range(threads)))
+                parts = list(pool.map(lambda k: run_oracle(oracle, og, app, B, pkw, roots_np, seed, per, k * per),
+                                      range(threads)))
             dt_all = time.perf_counter() - t
-            cpu_baseline["all_cores"] = {"value": round(sum(parts) / dt_all, 1), "cores": threads,
-                                         "sample": f"{threads} threads x {per} roots each, {dt_all:.1f} s"}
+            for k, (_, _, o_part) in enumerate(parts):
+                for i, x in enumerate(o_part):
+                    x = np.asarray(x)
+                    whole = np.asarray(o_single[i])
+                    if whole.ndim == 1:                       # walks: [S] per step
+                        ref = whole[k * per:(k + 1) * per]
+                    else:                                     # k-hop, layer: [samples, width] per step
+                        ref = whole[k * per // unit:(k + 1) * per // unit]
+                    assert np.array_equal(x.reshape(-1), ref.reshape(-1)), "threaded and single-threaded oracle differ"
+            baseline["all_cores"] = {"value": round(sum(q[0] for q in parts) / dt_all, 1), "cores": threads,
+                                     "sample": f"{threads} threads x {per} roots each (the same roots), {dt_all:.1f} s; "
+                                               "output identical to the single-threaded one"}
 
-    line = {
-        "metric": "sampled vertices/sec per step-batch on 1 MI355X; achieved HBM GB/s vs peak",
-        "value": round(value, 1), "unit": "sampled vertices/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+    res = {
+        "value": round(value, 1), "unit": "sampled vertices/s", "ms_per_step": round(ms_per_step, 4),
         "ms_per_call_median": round(per_call[len(per_call) // 2], 4), "ms_per_call_min": round(per_call[0], 4),
-        "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "int32", "data": "synthetic",
-        "config": {"workload": args.workload, "description": desc, "mode": args.mode,
-                   "group_bits": args.group_bits,
-                   "graph": g.describe(), "roots": int(roots.numel()), "seed": seed,
+        "config": {"workload": name, "description": desc, "mode": args.mode, "group_bits": args.group_bits,
+                   "window": args.window, "graph": g.describe(), "roots": int(roots.numel()), "seed": seed,
                    "slots_per_step": slots, "non_null_per_step": live},
         "slots_per_s": round(slots / (ms_per_step * 1e-3), 1),
         "phase_ms_per_step": {k: round(v, 4) for k, v in phase_ms.items()},
-        "roofline": roofline, "cpu_baseline": cpu_baseline,
+        "roofline": roofline, "parity_probe": parity_probe, "cpu_baseline": baseline,
     }
     if stats is not None:
-        line["scheduling"] = {"live_pairs": [int(x) for x in stats[:2, 0]] + ([int(stats[-1, 0])] if len(stats) > 2 else []),
-                              "distinct_transits": [int(x) for x in stats[:2, 1]],
-                              "sub_wg_grid": [[int(x) for x in stats[i, 2:5]] for i in range(min(2, len(stats)))]}
+        res["scheduling"] = {"live_pairs": [int(x) for x in stats[:2, 0]] + ([int(stats[-1, 0])] if len(stats) > 2 else []),
+                             "distinct_transits": [int(x) for x in stats[:2, 1]],
+                             "sub_wg_grid": [[int(x) for x in stats[i, 2:5]] for i in range(min(2, len(stats)))]}
+    del s, out, dg
+    torch.cuda.empty_cache()
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default=None, choices=sorted(WORKLOADS) + ["copy_calib", "c4_layer_edges"],
+                    help="default: c5_khop, with c5_deepwalk under \"also\"")
+    ap.add_argument("--mode", default="tp", choices=["tp", "sp"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--sub-max", type=int, default=0)
+    ap.add_argument("--wg-max", type=int, default=0)
+    ap.add_argument("--group-bits", type=int, default=0,
+                    help="0: exact transit grouping (default); b: group by the top b bits of the vertex id only")
+    ap.add_argument("--window", type=int, default=0,
+                    help="walks: 0 windows of samples in LDS (default), -1 GPU-wide grouping, 1024 / 2048 window size")
+    ap.add_argument("--force-class", type=int, default=-1,
+                    help="ablation: -1 balanced (default), 0/1/2 every transit sub-wavefront/workgroup/grid")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only; sampling shards by samples with the "
+              "graph replicated, which one GPU cannot show (use --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2009_06693_amd import binding as B
+    from paper_2009_06693_amd import inputs
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.workload == "copy_calib":
+        # A plain device-to-device copy of known size: the yardstick that turns the
+        # FETCH_SIZE / WRITE_SIZE counters of a profiler run into bytes.
+        nbytes, ms, gbps = measure_copy_gbps(torch, args.steps)
+        print(json.dumps({"workload": "copy_calib", "bytes_read": nbytes, "bytes_written": nbytes,
+                          "ms_per_copy": round(ms, 4), "copy_GBps": round(gbps, 1)}))
+        return
+    if args.workload == "c4_layer_edges":
+        return bench_layer_edges(args, B, inputs, torch, np)
+
+    primary = args.workload or "c5_khop"
+    res = run_workload(primary, args, B, inputs, torch, np, cpu_baseline=not args.no_cpu_baseline)
+    also = None
+    if args.workload is None:
+        also = run_workload("c5_deepwalk", args, B, inputs, torch, np, cpu_baseline=False)
+    _, _, copy_gbps = measure_copy_gbps(torch)
+    res["roofline"]["copy_GBps"] = round(copy_gbps, 1)
+    line = {
+        "metric": "sampled vertices/sec per step-batch on 1 MI355X; achieved HBM GB/s vs peak",
+        "value": res["value"], "unit": res["unit"], "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": res["ms_per_step"], "ms_per_call_median": res["ms_per_call_median"],
+        "ms_per_call_min": res["ms_per_call_min"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "int32", "data": "synthetic",
+    }
+    for k in ("config", "slots_per_s", "phase_ms_per_step", "roofline", "parity_probe", "cpu_baseline", "scheduling"):
+        if k in res:
+            line[k] = res[k]
+    if also is not None:
+        also["roofline"]["copy_GBps"] = round(copy_gbps, 1)
+        also.pop("cpu_baseline", None)
+        line["also"] = also
     print(json.dumps(line))
 
 

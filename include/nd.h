@@ -11,7 +11,9 @@
  * step are grouped by transit vertex with a radix sort and a segmented scan,
  * the transits are split into three scheduling classes by the number of
  * neighbours they must produce (Section 6.1.2, Table "Types of kernels"), and
- * one kernel per class draws the neighbours.
+ * one launch per step draws the neighbours of all three classes.  Random walks
+ * by default group per window of samples inside a workgroup's LDS instead
+ * (nd_params.sched_window).
  *
  * Conventions
  *   - All functions return 0 on success or a negative nd_status code; the
@@ -130,7 +132,19 @@ typedef struct nd_params {
                                /* segment scan or classification; every draw then goes    */
                                /* through the lane-per-draw kernel, which needs transits  */
                                /* to be near each other, not equal.  Same output.         */
-    int32_t reserved[3];
+    int32_t sched_window;      /* random walks: scope of the grouping by transit.              */
+                               /* -1: all samples of the call (GPU-wide sort and scan, three   */
+                               /* classes); 256, 1024 or 2048: windows of that many            */
+                               /* consecutive samples, each kept by one workgroup for the      */
+                               /* whole walk (pairs per transit counted in LDS; a transit with */
+                               /* many pairs in its window is sorted out, grouped and served   */
+                               /* workgroup-wide from LDS, the others lane-per-pair;           */
+                               /* sched_sub_max then is the largest number of pairs of one     */
+                               /* transit in a window served lane-per-pair, default 63; no     */
+                               /* grid class); 0: windows for walks unless sched_force_class,  */
+                               /* sched_sub_max, sched_wg_max or sched_group_bits is set.      */
+                               /* Same output.                                                 */
+    int32_t reserved[2];
 } nd_params;
 
 typedef struct nd_graph nd_graph; /* opaque; owned by the library */
@@ -350,7 +364,7 @@ int nd_samples_pack(const int32_t* const* step_out_dev, int32_t num_steps, const
  * ms[ND_PHASE_COUNT] and intervals[ND_PHASE_COUNT] (the caller zeroes them),
  * and resets the recording.  At most 16384 events are kept between reads;
  * later marks are dropped and nd_profile_read then returns ND_ERR_BAD_ARGUMENT.
- * The sampling phase contains exactly one kernel launch per step.
+ * The sampling phases contain exactly one kernel launch per interval.
  */
 typedef enum nd_phase {
     ND_PHASE_NONE = -1,
@@ -362,7 +376,9 @@ typedef enum nd_phase {
     ND_PHASE_SAMPLE_SP = 5,   /* sample-parallel kernel (ablation mode)             */
     ND_PHASE_LAYER = 6,       /* collective (layer) kernel                          */
     ND_PHASE_UNIQUE = 7,      /* duplicate removal and refill (unique neighbours)   */
-    ND_PHASE_COUNT = 8
+    ND_PHASE_WALK_WINDOW = 8, /* walk kernel with per-window grouping in LDS (one   */
+                              /* launch per 128 steps)                              */
+    ND_PHASE_COUNT = 9
 } nd_phase;
 int nd_profile_enable(int on);
 int nd_profile_read(double* ms, int64_t* intervals);

@@ -34,7 +34,7 @@ EXPORTS = ["nd_params_init", "nd_graph_create", "nd_graph_destroy", "nd_graph_in
            "nd_group_by_transit", "nd_layer_edges_workspace_bytes", "nd_layer_edges_count",
            "nd_layer_edges_fill", "nd_layer_edges_status", "nd_samples_pack", "nd_profile_enable", "nd_profile_read", "nd_last_error", "nd_version"]
 
-ND_PHASES = ["init", "sort", "group", "sample_sub", "sample_wg", "sample_sp", "layer", "unique"]
+ND_PHASES = ["init", "sort", "group", "sample_sub", "sample_wg", "sample_sp", "layer", "unique", "walk_window"]
 
 
 class nd_params(ctypes.Structure):
@@ -57,7 +57,8 @@ class nd_params(ctypes.Structure):
         ("lds_stage_policy", ctypes.c_int32),
         ("unique_rounds", ctypes.c_int32),
         ("sched_group_bits", ctypes.c_int32),
-        ("reserved", ctypes.c_int32 * 3),
+        ("sched_window", ctypes.c_int32),
+        ("reserved", ctypes.c_int32 * 2),
     ]
 
 

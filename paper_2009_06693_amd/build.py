@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libnd.so")
-SOURCES = ["nd_api.hip", "nd_graph.hip", "nd_sort.hip", "nd_sched.hip", "nd_sample.hip", "nd_layer.hip", "nd_edges.hip", "nd_pack.hip"]
+SOURCES = ["nd_api.hip", "nd_graph.hip", "nd_sort.hip", "nd_sched.hip", "nd_sample.hip", "nd_walk.hip", "nd_layer.hip", "nd_edges.hip", "nd_pack.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

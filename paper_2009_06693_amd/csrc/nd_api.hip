@@ -44,6 +44,8 @@ struct Plan {
     size_t hist_bytes = 0;     // largest histogram over the steps' sort plans
     int64_t state_len = 0;     // multi-dimensional walk: vertices in the samples' root sets
     size_t o_state = 0, o_transits = 0;
+    int window = 0;            // walks grouped per window of this many samples (0: GPU-wide grouping)
+    uint32_t heavy_min = 64;   // pairs of one transit in a window from which the workgroup class serves it
 };
 
 int64_t step_fanout(int app, const nd_params* p, int i) {
@@ -101,6 +103,15 @@ int check_params(const Graph& g, int app, const nd_params* p, int64_t num_roots,
         (p->sched_group_bits > 0 && p->sched_force_class != ND_CLASS_AUTO &&
          p->sched_force_class != ND_CLASS_SUBWAVE)) {
         set_error("bad scheduling override");
+        return ND_ERR_BAD_ARGUMENT;
+    }
+    if (p->sched_window != 0 && p->sched_window != -1 && p->sched_window != 256 && p->sched_window != 1024 &&
+        p->sched_window != 2048) {
+        set_error("sched_window must be 0, -1, 256, 1024 or 2048");
+        return ND_ERR_BAD_ARGUMENT;
+    }
+    if (p->sched_window > 0 && (!walk || p->sched_group_bits > 0 || p->sched_force_class == ND_CLASS_GRID)) {
+        set_error("sched_window applies to random walks, without sched_group_bits and without the grid class");
         return ND_ERR_BAD_ARGUMENT;
     }
     pl->app = app;
@@ -176,6 +187,15 @@ int check_params(const Graph& g, int app, const nd_params* p, int64_t num_roots,
             }
         }
     }
+    pl->window = 0;
+    if (walk && p->mode == ND_MODE_TRANSIT_PARALLEL) {
+        const bool overridden = p->sched_force_class != ND_CLASS_AUTO || p->sched_sub_max != 0 ||
+                                p->sched_wg_max != 0 || p->sched_group_bits != 0;
+        if (p->sched_window > 0) pl->window = p->sched_window;
+        else if (p->sched_window == 0 && !overridden) pl->window = walk_window_auto(pl->S);
+        if (pl->window > 0 && p->sched_window > 0 && p->sched_sub_max > 0)
+            pl->heavy_min = (uint32_t)p->sched_sub_max + 1u;
+    }
     pl->max_slots = 0;
     pl->max_out = 0;
     double guard = 1.0;
@@ -212,7 +232,7 @@ void layout(Plan* pl, int64_t V) {
         pl->o_state = o; o = align_up(o + (size_t)(pl->state_len > 0 ? pl->state_len : 1) * 4);
         pl->o_transits = o; o = align_up(o + (size_t)(pl->S > 0 ? pl->S : 1) * 4);
     }
-    if (pl->mode == ND_MODE_TRANSIT_PARALLEL && !pl->collective) {
+    if (pl->mode == ND_MODE_TRANSIT_PARALLEL && !pl->collective && pl->window == 0) {
         const size_t n = (size_t)(pl->max_slots > 0 ? pl->max_slots : 1);
         pl->o_keysA = o; o = align_up(o + n * 4);
         pl->o_valsA = o; o = align_up(o + n * 4);
@@ -552,6 +572,14 @@ static int sample_impl(const nd_graph* h, int app, const nd_params* params, cons
     int32_t* mrw_state = (int32_t*)(ws + pl.o_state);
     int32_t* mrw_transits = (int32_t*)(ws + pl.o_transits);
     const uint32_t mrw_R = (uint32_t)params->roots_per_sample;
+    if (pl.window > 0) {  // walks grouped per window of samples, inside LDS
+        rc = walk_windows(g, draw, multirw, a, pl.S, pl.k, pl.window, pl.heavy_min, params->sched_force_class,
+                          roots_dev, 1, step_out_dev, &hdr->status, ctl, multirw ? mrw_state : nullptr,
+                          multirw ? mrw_R : 1u, stream);
+        if (rc != ND_OK) return rc;
+        mark_phase(ND_PHASE_NONE, stream);
+        return ND_OK;
+    }
     if (multirw) {
         rc = multirw_init(g, roots_dev, pl.state_len, mrw_state, &hdr->status, stream);
         if (rc != ND_OK) return rc;

@@ -58,6 +58,17 @@ int multirw_select(const int32_t* state, int64_t S, uint32_t R, uint64_t seed, u
 int multirw_update(int32_t* state, int64_t S, uint32_t R, uint64_t seed, uint32_t sample_base,
                    uint32_t step, const int32_t* added, hipStream_t stream);
 
+// Random walks grouped per window of samples (nd_walk.hip): all num_steps steps of DeepWalk, PPR,
+// node2vec or the multi-dimensional walk, one launch per 128 steps.  d carries the draw's
+// constants (seed, sample_base, PPR threshold, node2vec biases, LDS policy); window is 256, 1024 or
+// 2048; heavy_min the number of pairs of one transit inside a window from which the whole
+// workgroup serves it; ctl (may be null) receives per-step counters.
+int walk_window_auto(int64_t S);
+int walk_windows(const Graph& gr, int draw, bool multirw, const DrawArgs& d, int64_t S, int32_t num_steps,
+                 int window, uint32_t heavy_min, int force_class, const int32_t* roots, int check_roots,
+                 int32_t* const* step_out, uint32_t* status, StepCtl* ctl, int32_t* mrw_state, uint32_t R,
+                 hipStream_t stream);
+
 // Unique neighbours (Section 6.3) for one k-hop step whose first draw round has already been
 // written to `out`: per sample, duplicates are removed (the lowest slot keeps the vertex) and
 // the slots that lost draw again, sample-parallel, for rounds - 1 further attempts.

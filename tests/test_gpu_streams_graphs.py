@@ -17,7 +17,8 @@ _small = inputs.small_graph()
 
 
 @pytest.mark.parametrize("app,kw", [(B.ND_KHOP, dict(num_steps=2, fanout=[6, 5])),
-                                    (B.ND_DEEPWALK, dict(num_steps=15)),
+                                    (B.ND_DEEPWALK, dict(num_steps=15)),                  # windows in LDS
+                                    (B.ND_DEEPWALK, dict(num_steps=15, sched_window=-1)),  # GPU-wide grouping
                                     (B.ND_KHOP, dict(num_steps=2, fanout=[6, 5], sched_group_bits=6))])
 def test_graph_replay_matches_eager(app, kw):
     g = _small
