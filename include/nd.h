@@ -177,7 +177,12 @@ int nd_graph_create(nd_graph** out, int64_t V, int64_t E, const void* row_offset
                     int offsets_are_int64, const int32_t* col_indices,
                     const float* weights_or_null, int src_is_device, void* hip_stream);
 
-/* Frees the device copy.  Accepts NULL. */
+/*
+ * Ends the life of the graph's device copy (Section 5.1: the graph stays in GPU
+ * global memory for as long as samples are drawn from it; Section 6.4: one copy
+ * per GPU).  Frees everything nd_graph_create allocated.  Accepts NULL.  No
+ * nd_sample call on this graph may still be running.
+ */
 int nd_graph_destroy(nd_graph* g);
 
 /* V, E, whether weights are present, and the width of the stored offsets. */
@@ -185,7 +190,10 @@ int nd_graph_info(const nd_graph* g, int64_t* V, int64_t* E, int* has_weights,
                   int* offsets_are_int64);
 
 /*
- * Sizes of one nd_sample call.
+ * Sizes of one nd_sample call (Section 4.1, "Output format": the second form,
+ * one array per step whose length follows from the number of samples and the
+ * application's steps(), stepSize(i) and sampleSize(i); Section 4.1's
+ * stepTransits fixes how many transits, hence slots, step i has).
  *   num_roots        walks and k-hop: one sample per root; layer and multi-
  *                    dimensional walk: a multiple of roots_per_sample (one sample
  *                    per group of consecutive roots)
@@ -200,8 +208,12 @@ int nd_sample_query(const nd_graph* g, int app, const nd_params* params, int64_t
                     int32_t* num_steps, int64_t* step_len, size_t* workspace_bytes);
 
 /*
- * Runs every step of the application for all roots, asynchronously on
- * hip_stream, allocating nothing.
+ * Runs every step of the application for all roots (Section 3: starting from
+ * the initial samples, each step takes the step's transit vertices of every
+ * sample and adds vertices drawn from their neighbourhoods, individually per
+ * transit or collectively per sample; Section 4.1: the run ends after steps()
+ * steps; Section 5.2 and Section 6: every step is executed transit-parallel),
+ * asynchronously on hip_stream, allocating nothing.
  *
  *   roots_dev        device, num_roots int32 vertices.  A root outside [0, V) is
  *                    treated as NULL and recorded (see nd_sample_status).
@@ -383,7 +395,11 @@ typedef enum nd_phase {
 int nd_profile_enable(int on);
 int nd_profile_read(double* ms, int64_t* intervals);
 
+/* Message of the last failure of a call of this library on the calling thread (the paper's system
+ * reports errors through its host program; this ABI returns a status code and keeps the text here).
+ * The pointer stays valid until the thread's next failing call. */
 const char* nd_last_error(void);
+/* ND_VERSION of the loaded library. */
 int nd_version(void);
 
 #ifdef __cplusplus

@@ -6,6 +6,7 @@
 #include <new>
 
 #include "nd_common.h"
+#include "nd_wave.h"
 
 namespace nd {
 
@@ -37,43 +38,57 @@ __global__ void check_offsets_kernel(const OffT* __restrict__ off, int64_t V, in
     if (bad) atomicOr(flags, bad);
 }
 
-// One thread per row: columns in range and strictly ascending; with weights,
-// quantise (w_q = floor(w * 2^16 + 0.5), evaluated in double), accumulate the
-// running sums and the row maximum.
+// One wavefront per row, 64 entries at a time: columns in range and strictly
+// ascending; with weights, quantise (w_q = floor(w * 2^16 + 0.5), evaluated in
+// double), accumulate the running sums (a wave scan per 64 entries plus the sum
+// carried from the entries before) and the row maximum.  Rows are dealt to the
+// wavefronts round robin, so a row of any length costs its wavefront
+// ceil(deg / 64) rounds and the long rows of a skewed graph do not serialise.
 template <typename OffT>
-__global__ void check_rows_kernel(const OffT* __restrict__ off, const int32_t* __restrict__ col,
-                                  const float* __restrict__ w, int64_t V,
-                                  uint32_t* __restrict__ wq, uint64_t* __restrict__ cumq,
-                                  uint32_t* __restrict__ maxwq, uint32_t* __restrict__ flags) {
-    const int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (v >= V) return;
+__global__ __launch_bounds__(256) void check_rows_kernel(const OffT* __restrict__ off, const int32_t* __restrict__ col,
+                                                         const float* __restrict__ w, int64_t V,
+                                                         uint32_t* __restrict__ wq, uint64_t* __restrict__ cumq,
+                                                         uint32_t* __restrict__ maxwq, uint32_t* __restrict__ flags) {
+    const int lane = lane_id();
+    const int64_t wave0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 6;
+    const int64_t n_waves = ((int64_t)gridDim.x * 256) >> 6;
     uint32_t bad = 0;
-    int64_t prev = -1;
-    uint64_t run = 0;
-    uint32_t mx = 0;
-    const int64_t lo = (int64_t)off[v], hi = (int64_t)off[v + 1];
-    for (int64_t e = lo; e < hi; ++e) {
-        const int64_t c = col[e];
-        if (c < 0 || c >= V) bad |= kBadColumn;
-        if (c <= prev) bad |= kBadOrder;
-        prev = c;
-        if (w) {
-            const float x = w[e];
-            uint32_t q = 1;
-            if (!(x > 0.0f) || !(x < 32768.0f)) {
-                bad |= kBadWeight;
-            } else {
-                q = (uint32_t)floor((double)x * 65536.0 + 0.5);
+    for (int64_t v = wave0; v < V; v += n_waves) {  // the same v on every lane of the wave
+        const int64_t lo = (int64_t)off[v], hi = (int64_t)off[v + 1];
+        unsigned long long run = 0;
+        uint32_t mx = 0;
+        for (int64_t base = lo; base < hi; base += 64) {
+            const int64_t e = base + lane;
+            const bool in = e < hi;
+            const int32_t c = in ? col[e] : 0;
+            int32_t before = __shfl_up(c, 1, 64);
+            if (lane == 0) before = e > lo ? col[e - 1] : -1;
+            if (in && (c < 0 || (int64_t)c >= V)) bad |= kBadColumn;
+            if (in && c <= before) bad |= kBadOrder;
+            if (w) {
+                uint32_t q = 0;
+                if (in) {
+                    const float x = w[e];
+                    q = 1;
+                    if (!(x > 0.0f) || !(x < 32768.0f)) bad |= kBadWeight;
+                    else q = (uint32_t)floor((double)x * 65536.0 + 0.5);
+                    wq[e] = q;
+                    if (q > mx) mx = q;
+                }
+                const unsigned long long incl = wave_inclusive_scan((unsigned long long)q, lane);
+                if (in) cumq[e] = run + incl;
+                run += __shfl(incl, 63, 64);
             }
-            wq[e] = q;
-            run += q;
-            cumq[e] = run;
-            if (q > mx) mx = q;
         }
-    }
-    if (w) {
-        maxwq[v] = mx;
-        if (run >= (1ull << 39)) bad |= kBadRowTotal;
+        if (w) {
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) {
+                const uint32_t o = __shfl_xor(mx, d, 64);
+                mx = o > mx ? o : mx;
+            }
+            if (lane == 0) maxwq[v] = mx;
+            if (run >= (1ull << 39)) bad |= kBadRowTotal;
+        }
     }
     if (bad) atomicOr(flags, bad);
 }
@@ -110,8 +125,13 @@ int validate_and_build(Graph* g, const float* w_dev, uint32_t* flags_dev, hipStr
         return ND_ERR_BAD_GRAPH;
     }
     // rows may only be walked once the offsets are known to be sane
-    hipLaunchKernelGGL(check_rows_kernel<OffT>, dim3((unsigned)blocks), dim3(threads), 0, stream,
-                       (const OffT*)g->off, g->col, w_dev, g->V, g->wq, g->cumq, g->maxwq, flags_dev);
+    {   // one wavefront per row; enough workgroups to fill the chip several times, never more than rows / 4
+        int64_t row_blocks = (g->V + 3) / 4;
+        const int64_t cap = (int64_t)g->num_cus * 16;
+        if (row_blocks > cap) row_blocks = cap;
+        hipLaunchKernelGGL(check_rows_kernel<OffT>, dim3((unsigned)row_blocks), dim3(256), 0, stream,
+                           (const OffT*)g->off, g->col, w_dev, g->V, g->wq, g->cumq, g->maxwq, flags_dev);
+    }
     ND_HIP_CHECK(hipGetLastError());
     ND_HIP_CHECK(hipMemcpyAsync(&flags, flags_dev, sizeof(flags), hipMemcpyDeviceToHost, stream));
     ND_HIP_CHECK(hipStreamSynchronize(stream));
