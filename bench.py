@@ -365,7 +365,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default=None, choices=sorted(WORKLOADS) + ["copy_calib", "c4_layer_edges"],
+    ap.add_argument("--workload", default=None, choices=sorted(WORKLOADS) + ["copy_calib", "store_calib", "c4_layer_edges"],
                     help="default: c5_khop, with c5_deepwalk under \"also\"")
     ap.add_argument("--mode", default="tp", choices=["tp", "sp"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -396,6 +396,41 @@ def main():
         nbytes, ms, gbps = measure_copy_gbps(torch, args.steps)
         print(json.dumps({"workload": "copy_calib", "bytes_read": nbytes, "bytes_written": nbytes,
                           "ms_per_copy": round(ms, 4), "copy_GBps": round(gbps, 1)}))
+        return
+    if args.workload == "store_calib":
+        # What scattered stores cost on this GPU: runs of run_len ints at scattered run-aligned places
+        # of a 2.7 GB array against whole 128-byte lines at scattered places and against stores in order.
+        n_runs = 1 << 26
+        buf = torch.empty(n_runs * 10, dtype=torch.int32, device="cuda:0")
+        rows = []
+        for what, runs, run_len, scattered in (("40-byte runs (10 ints), scattered", n_runs, 10, True),
+                                               ("4-byte runs, scattered", n_runs, 1, True),
+                                               ("64-byte runs (16 ints), scattered", 1 << 25, 16, True),
+                                               ("whole 128-byte lines (32 ints), scattered", 1 << 24, 32, True),
+                                               ("40-byte runs in order", n_runs, 10, False),
+                                               ("40-byte runs, scattered inside 16 windows of 168 MB, one launch per window",
+                                                n_runs, 10, 16),
+                                               ("40-byte runs, scattered inside 64 windows of 42 MB, one launch per window",
+                                                n_runs, 10, 64)):
+            def go():
+                if scattered is True or scattered is False:
+                    B.nd_probe_store_runs(buf, runs, run_len, scattered)
+                else:                                    # `scattered` windows, each its own launch
+                    per = runs // scattered
+                    for w in range(scattered):
+                        B.nd_probe_store_runs(buf[w * per * run_len:(w + 1) * per * run_len], per, run_len, True)
+            go()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.steps):
+                go()
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / args.steps
+            rows.append({"pattern": what, "runs": runs, "ms": round(ms, 4), "runs_per_s": round(runs / (ms * 1e-3), 1),
+                         "payload_GBps": round(runs * run_len * 4 / (ms * 1e-3) / 1e9, 1)})
+        print(json.dumps({"workload": "store_calib", "patterns": rows}))
         return
     if args.workload == "c4_layer_edges":
         return bench_layer_edges(args, B, inputs, torch, np)

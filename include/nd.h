@@ -395,6 +395,19 @@ typedef enum nd_phase {
 int nd_profile_enable(int on);
 int nd_profile_read(double* ms, int64_t* intervals);
 
+/*
+ * Store-pattern probe, for measurement (Section 6.1.1: the point of sub-warp
+ * execution is that a sample's new vertices leave in one coalesced write; this
+ * call measures what such writes cost on this GPU when the runs land at
+ * scattered places, as they do after grouping by transit).  Writes n_runs runs of
+ * run_len int32 each into out_dev (n_runs * run_len entries; n_runs a power of
+ * two, run_len in [1, 32]): run r goes to run position mix(r), a fixed pseudo-random
+ * bijection of [0, n_runs), when scattered != 0, to position r otherwise; every entry of out_dev is
+ * written exactly once.  Asynchronous on hip_stream; allocates nothing.
+ * Errors: ND_ERR_NULL_POINTER, ND_ERR_BAD_ARGUMENT, ND_ERR_HIP.
+ */
+int nd_probe_store_runs(int32_t* out_dev, int64_t n_runs, int32_t run_len, int scattered, void* hip_stream);
+
 /* Message of the last failure of a call of this library on the calling thread (the paper's system
  * reports errors through its host program; this ABI returns a status code and keeps the text here).
  * The pointer stays valid until the thread's next failing call. */

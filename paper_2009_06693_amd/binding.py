@@ -32,7 +32,7 @@ ND_ERR_NO_WEIGHTS, ND_ERR_WORKSPACE, ND_ERR_HIP, ND_ERR_BAD_ROOT, ND_ERR_TOO_LAR
 EXPORTS = ["nd_params_init", "nd_graph_create", "nd_graph_destroy", "nd_graph_info", "nd_sample_query",
            "nd_sample", "nd_sample_static", "nd_sample_status", "nd_sample_stats", "nd_group_workspace_bytes",
            "nd_group_by_transit", "nd_layer_edges_workspace_bytes", "nd_layer_edges_count",
-           "nd_layer_edges_fill", "nd_layer_edges_status", "nd_samples_pack", "nd_profile_enable", "nd_profile_read", "nd_last_error", "nd_version"]
+           "nd_layer_edges_fill", "nd_layer_edges_status", "nd_samples_pack", "nd_probe_store_runs", "nd_profile_enable", "nd_profile_read", "nd_last_error", "nd_version"]
 
 ND_PHASES = ["init", "sort", "group", "sample_sub", "sample_wg", "sample_sp", "layer", "unique", "walk_window"]
 
@@ -119,6 +119,8 @@ def lib() -> ctypes.CDLL:
         L.nd_layer_edges_status.argtypes = [vp, vp]
         L.nd_samples_pack.restype = ctypes.c_int
         L.nd_samples_pack.argtypes = [vp, i32, ctypes.POINTER(i64), i64, vp, vp]
+        L.nd_probe_store_runs.restype = ctypes.c_int
+        L.nd_probe_store_runs.argtypes = [vp, i64, i32, ctypes.c_int, vp]
         L.nd_profile_enable.restype = ctypes.c_int
         L.nd_profile_enable.argtypes = [ctypes.c_int]
         L.nd_profile_read.restype = ctypes.c_int
@@ -325,6 +327,13 @@ def nd_samples_pack(step_out: Sequence[torch.Tensor], num_samples: int, samples:
     _check(lib().nd_samples_pack(ptrs, k, lens, num_samples, samples.data_ptr() if samples.numel() else None,
                                  _stream_ptr(stream)))
     return samples
+
+
+def nd_probe_store_runs(out: torch.Tensor, n_runs: int, run_len: int, scattered: bool, stream=None):
+    """Measurement: writes n_runs runs of run_len int32 into `out` (n_runs * run_len entries)."""
+    if out.dtype != torch.int32 or not out.is_cuda or out.numel() < n_runs * run_len:
+        raise TypeError("out must be an int32 CUDA tensor of n_runs * run_len entries")
+    _check(lib().nd_probe_store_runs(out.data_ptr(), n_runs, run_len, int(scattered), _stream_ptr(stream)))
 
 
 def nd_layer_edges_workspace_bytes(num_samples: int, n_prev: int) -> int:

@@ -945,6 +945,18 @@ int nd_layer_edges_status(const void* workspace_dev, void* hip_stream) {
     return ND_OK;
 }
 
+int nd_probe_store_runs(int32_t* out_dev, int64_t n_runs, int32_t run_len, int scattered, void* hip_stream) {
+    if (!out_dev) {
+        set_error("out_dev is NULL");
+        return ND_ERR_NULL_POINTER;
+    }
+    if (n_runs < 1 || n_runs >= (1ll << 31) || (n_runs & (n_runs - 1)) != 0 || run_len < 1 || run_len > 32) {
+        set_error("n_runs must be a power of two below 2^31 and run_len in [1, 32]");
+        return ND_ERR_BAD_ARGUMENT;
+    }
+    return probe_store_runs(out_dev, n_runs, run_len, scattered, (hipStream_t)hip_stream);
+}
+
 int nd_samples_pack(const int32_t* const* step_out_dev, int32_t num_steps, const int64_t* step_len,
                     int64_t num_samples, int32_t* samples_dev, void* hip_stream) {
     if (num_steps < 1 || num_steps > ND_MAX_WALK_STEPS || num_samples < 0) {

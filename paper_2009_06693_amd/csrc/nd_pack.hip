@@ -54,7 +54,42 @@ __global__ __launch_bounds__(256) void pack_wide_kernel(const int32_t* __restric
     samples[(int64_t)s * rec_len + first_col + j] = src[e];
 }
 
+// Measurement only: n_runs runs of run_len ints, one lane per int, run r at run position
+// mix(r) (a bijection of [0, n_runs) for a power of two: odd multiplications and xor-shifts) or at r.
+__device__ __forceinline__ uint32_t probe_mix(uint32_t x, uint32_t mask, int half) {
+    x = (x * 0x9E3779B1u) & mask;
+    x ^= x >> half;
+    x = (x * 0x85EBCA6Bu) & mask;
+    x ^= x >> half;
+    x = (x * 0xC2B2AE35u) & mask;
+    x ^= x >> half;
+    return x;
+}
+
+__global__ __launch_bounds__(256) void probe_store_runs_kernel(int32_t* __restrict__ out, uint32_t n_runs,
+                                                               FastDiv div_len, int scattered, int half) {
+    // a 256-lane round covers 256 / run_len whole runs; a lane keeps its place j inside the run
+    const uint32_t len = div_len.d;
+    const uint32_t r_local = fastdiv(threadIdx.x, div_len), j = threadIdx.x - r_local * len;
+    const uint32_t per_round = 256u / len;
+    if (r_local >= per_round) return;
+    for (uint64_t r = (uint64_t)blockIdx.x * per_round + r_local; r < n_runs; r += (uint64_t)gridDim.x * per_round) {
+        const uint32_t dst = scattered ? probe_mix((uint32_t)r, n_runs - 1u, half) : (uint32_t)r;
+        out[(uint64_t)dst * len + j] = (int32_t)r;
+    }
+}
+
 }  // namespace
+
+int probe_store_runs(int32_t* out, int64_t n_runs, int32_t run_len, int scattered, hipStream_t stream) {
+    if (n_runs == 0) return ND_OK;
+    int bits = 0;
+    while ((1ll << bits) < n_runs) ++bits;
+    hipLaunchKernelGGL(probe_store_runs_kernel, dim3(2048), dim3(256), 0, stream, out, (uint32_t)n_runs,
+                       make_fastdiv((uint32_t)run_len), scattered, bits / 2 + 1);
+    ND_HIP_CHECK(hipGetLastError());
+    return ND_OK;
+}
 
 int pack_samples(const int32_t* const* step_out, int32_t num_steps, const int64_t* step_len, int64_t S,
                  int32_t* samples, hipStream_t stream) {
