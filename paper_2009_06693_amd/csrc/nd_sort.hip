@@ -2,9 +2,9 @@
 // digit radix sort on the transit id, hand-written for gfx950.
 //
 // This is the first stage of the scheduling index of Section 6.1.2 of the
-// paper ("creates a transit-to-sample map"), which Section 8.1 reports as a
-// radix sort of the samples keyed on the transit.  The paper used a vendor
-// sort; here each pass is three kernels:
+// paper (the map from every transit to the samples that hold it), which
+// Section 8.1 reports as a radix sort of the samples keyed on the transit.
+// The paper used a vendor sort; here each pass is three kernels:
 //   upsweep    per-tile digit histogram in LDS              (reads 4 B / pair)
 //   binscan    per-digit exclusive scan over the tiles
 //   downsweep  stable in-tile ranking with wave64 ballots, tile-local reorder

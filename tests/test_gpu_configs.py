@@ -69,9 +69,11 @@ def test_config1_deepwalk_full():
     og = oracle.OracleGraph(g.row_offsets, g.col_indices)
     roots = inputs.all_vertices_roots(g)
     want = oracle.deepwalk(og, roots, 100, seed=1)
-    for mode in (TP, SP):
-        _, out = _run(dg, B.ND_DEEPWALK, roots, 1, num_steps=100, mode=mode)
-        assert_steps_equal([o.cpu().numpy() for o in out], list(want), f"config 1 mode {mode}")
+    # transit-parallel with the grouping per window (the default for walks), with the GPU-wide
+    # grouping of Section 6.1.2, and sample-parallel
+    for kw in (dict(mode=TP), dict(mode=TP, sched_window=-1), dict(mode=SP)):
+        _, out = _run(dg, B.ND_DEEPWALK, roots, 1, num_steps=100, **kw)
+        assert_steps_equal([o.cpu().numpy() for o in out], list(want), f"config 1 {kw}")
 
 
 def test_config2_node2vec_and_ppr_full():
@@ -80,13 +82,13 @@ def test_config2_node2vec_and_ppr_full():
     og = oracle.OracleGraph(g.row_offsets, g.col_indices, g.weights)
     roots = inputs.all_vertices_roots(g)
     want = oracle.node2vec(og, roots, 100, 2.0, 0.5, seed=2, use_weights=True)
-    for mode in (TP, SP):
-        _, out = _run(dg, B.ND_NODE2VEC, roots, 2, num_steps=100, p=2.0, q=0.5, use_weights=1, mode=mode)
-        assert_steps_equal([o.cpu().numpy() for o in out], list(want), f"config 2 node2vec mode {mode}")
+    for kw in (dict(mode=TP), dict(mode=TP, sched_window=-1), dict(mode=SP)):
+        _, out = _run(dg, B.ND_NODE2VEC, roots, 2, num_steps=100, p=2.0, q=0.5, use_weights=1, **kw)
+        assert_steps_equal([o.cpu().numpy() for o in out], list(want), f"config 2 node2vec {kw}")
     want = oracle.ppr(og, roots, 100, 0.01, seed=2, use_weights=True)
-    for mode in (TP, SP):
-        s, out = _run(dg, B.ND_PPR, roots, 2, num_steps=100, term_prob=0.01, use_weights=1, mode=mode)
-        assert_steps_equal([o.cpu().numpy() for o in out], list(want), f"config 2 ppr mode {mode}")
+    for kw in (dict(mode=TP), dict(mode=TP, sched_window=-1), dict(mode=SP)):
+        s, out = _run(dg, B.ND_PPR, roots, 2, num_steps=100, term_prob=0.01, use_weights=1, **kw)
+        assert_steps_equal([o.cpu().numpy() for o in out], list(want), f"config 2 ppr {kw}")
     # mean walk length under termination probability 0.01 with cap 100 is about 63
     length = (want >= 0).sum(axis=0).mean()
     assert 55 < length < 70
@@ -243,8 +245,12 @@ def test_config5_khop_and_deepwalk():
         nxt = out[i] >= 0
         assert bool((nxt <= alive).all())
         alive = nxt
-    s2, out2 = _run(dg, B.ND_DEEPWALK, roots, 5, num_steps=100, sched_group_bits=6)
-    assert all(torch.equal(a, b) for a, b in zip(out, out2))
+    # the same walks through the GPU-wide scheduling index (sort, scan, three classes per step) and
+    # through grouping by the top 6 bits of the transit id only
+    for kw in (dict(sched_window=-1), dict(sched_group_bits=6), dict(sched_window=2048)):
+        s2, out2 = _run(dg, B.ND_DEEPWALK, roots, 5, num_steps=100, **kw)
+        assert all(torch.equal(a, b) for a, b in zip(out, out2)), kw
+        del s2, out2
 
 
 def test_unique_khop_on_the_large_graph():
