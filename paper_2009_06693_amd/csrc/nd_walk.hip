@@ -95,7 +95,7 @@ __global__ __launch_bounds__(THREADS) void walk_window_kernel(GraphView<OffT> g,
     __shared__ uint32_t s_hist[WAVES][256];
     __shared__ uint32_t s_digit_start[256];
     __shared__ uint32_t s_tmp[WAVES + 2];
-    __shared__ uint32_t s_cnt[2][4];         // per step (two sets used in turn): grouped pairs, live pairs,
+    __shared__ uint32_t s_cnt[3][4];         // per step (three sets used in turn): grouped pairs, live pairs,
                                              // distinct transits, heavy transits
 
     const int tid = threadIdx.x, lane = lane_id(), wv = wave_id();
@@ -107,7 +107,7 @@ __global__ __launch_bounds__(THREADS) void walk_window_kernel(GraphView<OffT> g,
     if (passes < 1) passes = 1;
 
     for (uint32_t i = tid; i < NB; i += THREADS) s_tab[i] = 0ull;  // tag 0: no step
-    if (tid < 8) (&s_cnt[0][0])[tid] = 0;
+    if (tid < 12) (&s_cnt[0][0])[tid] = 0;
 
     // ---- state of my slots: slot l = it * THREADS + tid of the window
     int32_t cur[ITEMS], prev[ITEMS];
@@ -153,7 +153,7 @@ __global__ __launch_bounds__(THREADS) void walk_window_kernel(GraphView<OffT> g,
         DrawArgs d = a.d;
         d.step = step;
         d.has_prev = step > 0;
-        uint32_t* cnt_now = s_cnt[si & 1u];
+        uint32_t* cnt_now = s_cnt[si % 3u];
         const unsigned long long tag = (unsigned long long)(si + 1u) << 48;
 
         // ---- 1. transit enumeration: every live slot enters its transit in the window's table
@@ -199,8 +199,11 @@ __global__ __launch_bounds__(THREADS) void walk_window_kernel(GraphView<OffT> g,
                 if (first_w) atomicAdd(&cnt_now[2], first_w);
                 if (live_w) atomicAdd(&cnt_now[1], live_w);
             }
-            if (tid == 0)  // the next step's set: thread 0 made its last reads of it at the end of the step before
-                for (int c = 0; c < 4; ++c) s_cnt[(si + 1u) & 1u][c] = 0;
+            // The next step's set was last used two steps ago.  A thread can lag behind thread 0 by
+            // less than one step (two barriers per step), so nobody can still be reading it; with
+            // two sets a thread that has not yet read this step's pair count could see it cleared.
+            if (tid == 0)
+                for (int c = 0; c < 4; ++c) s_cnt[(si + 1u) % 3u][c] = 0;
         }
         __syncthreads();
 
