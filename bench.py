@@ -30,7 +30,8 @@ HBM_PEAK_GBS = 8000.0
 # gives: x2.0 and x1.0), averaged over the launches of one call.  Sources: the counter tables in
 # profiles/c5_khop_tp_rocprofv3.md and profiles/c5_deepwalk_tp_rocprofv3.md.  None where not profiled.
 MEASURED_TRAFFIC_BYTES = {
-    ("c5_khop", "tp", "sample_sub"): int((281.4 + 2313.6 + 402.9 + 2918.0) / 2 * 1048576),
+    ("c5_khop", "tp", "sample_sub"): 3032585965,        # 1,236.4 MiB fetched + 1,655.7 MiB written per launch
+    ("c5_deepwalk", "tp", "walk_window"): 52886552369,  # 48,811.5 MiB fetched + 1,625.0 MiB written per launch
 }
 
 WORKLOADS = {
@@ -312,8 +313,14 @@ def run_workload(name, args, B, inputs, torch, np, cpu_baseline):
             got = out[i][: x.size].cpu().numpy()
             assert np.array_equal(got, x.reshape(-1)), f"{name}: GPU and oracle differ at step {i} (baseline sample)"
         parity_probe = f"first {n} roots, every step, equal to the oracle"
+        cpu_model = ""
+        try:
+            with open("/proc/cpuinfo") as f:
+                cpu_model = next((l.split(":", 1)[1].strip() for l in f if l.startswith("model name")), "")
+        except OSError:
+            pass
         baseline = {"value": round(live_cpu / dt_cpu, 1), "unit": "sampled vertices/s", "cores": 1,
-                    "kind": "oracle",
+                    "kind": "oracle", "cpu_model": cpu_model, "host_cpus": os.cpu_count(),
                     "sample": f"first {n} of {roots_np.size} roots of the same workload, "
                               f"{dt_cpu:.1f} s of single-threaded oracle time"}
         # The same oracle, unchanged, on disjoint ranges of the same sample from several host threads
