@@ -373,103 +373,201 @@ int launch_sp(const Graph& gr, const DrawArgs& a, const int32_t* src, int64_t n_
 }
 
 // ---------------------------------------------------------------- unique neighbours (Section 6.3)
-// One workgroup per sample.  The paper removes duplicates with a per-sample sort and scan;
+// One group of lanes per sample.  The paper removes duplicates with a per-sample sort and scan;
 // here the vertices a sample holds live in an LDS hash table (open addressing, at least twice
 // as many buckets as slots).  Every bucket remembers the best claim on its vertex: 0 once a
 // slot holds it, otherwise the lowest slot index (+1) proposing it this round - an atomicMin,
 // so the outcome does not depend on the order in which lanes arrive.  Slots that lose draw
-// again straight from the graph (the paper's sample-parallel refill).
-// The workgroup is sized to the sample: THREADS * kPerThread >= W slots, one wavefront for the
-// 25-slot first hop of GraphSAGE and, four slots per lane, for its 250-slot second hop.
+// again straight from the graph (the paper's sample-parallel refill).  A slot whose parent's
+// slots already hold as many distinct vertices as the parent's row has entries can only draw a
+// held vertex; it ends empty at once instead of drawing in vain for the rounds that are left.
+// The kernel is bound by instruction issue, so idle lanes are what it pays for:
+//  * the group is sized to the sample, THREADS * kPerThread >= W slots: half a wavefront for the
+//    25-slot first hop of GraphSAGE, a whole one, four slots per lane, for its 250-slot second hop;
+//  * after the first round the slots still open are few and scattered, so they are packed into a
+//    queue in LDS and the later rounds run lane-per-queue-entry, with the counter-based generator
+//    keyed by the slot the entry names;
+//  * groups of a wavefront or less share a 256-lane workgroup, each with its own table and queues,
+//    and every group walks over samples with a stride.
+template <int THREADS>
+__device__ __forceinline__ void group_sync() {
+    if (THREADS > 64) {
+        __syncthreads();
+    } else {  // part of one wavefront: its LDS operations complete in order; keep the compiler from moving them
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+// true when x is non-zero in any lane of the group; group_lanes: the group's lanes within its wavefront
+template <int THREADS>
+__device__ __forceinline__ int group_or(int x, uint64_t group_lanes) {
+    if (THREADS > 64) return __syncthreads_or(x);
+    group_sync<THREADS>();
+    const int r = (__ballot(x != 0) & group_lanes) != 0ull;
+    group_sync<THREADS>();
+    return r;
+}
+// A queue place for every lane with flag set (any order).  A group inside one wavefront counts in a
+// register (*fill, the same in all its lanes); a four-wavefront group counts in LDS (*fill_lds).
+// Every lane of the group calls it, in converged code.
+template <int THREADS>
+__device__ __forceinline__ uint32_t group_reserve(bool flag, uint64_t group_lanes, uint32_t* fill, uint32_t* fill_lds) {
+    const uint64_t votes = __ballot(flag) & group_lanes;
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t before = (uint32_t)__popcll(votes & ((1ull << lane) - 1ull));
+    const uint32_t n = (uint32_t)__popcll(votes);
+    if (THREADS > 64) {
+        uint32_t base = 0;
+        if (lane == 0 && n > 0) base = atomicAdd(fill_lds, n);
+        base = (uint32_t)__shfl((int)base, 0, 64);
+        return base + before;
+    }
+    const uint32_t base = *fill;
+    *fill = base + n;
+    return base + before;
+}
+
 template <typename OffT, int THREADS, int kPerThread>
-__global__ __launch_bounds__(THREADS) void unique_kernel(GraphView<OffT> g, UniqueArgs a) {
-    constexpr uint32_t kBuckets = 2 * THREADS * kPerThread;
-    __shared__ int32_t h_key[kBuckets];     // vertex of the bucket, NULL = empty
-    __shared__ uint32_t h_claim[kBuckets];  // 0 = held by a slot, else lowest proposing slot + 1
-    const uint32_t s = blockIdx.x;
+__global__ __launch_bounds__(256) void unique_kernel(GraphView<OffT> g, UniqueArgs a, uint32_t num_samples) {
+    static_assert(THREADS == 32 || THREADS == 64 || THREADS == 256, "a group is half a wavefront, one, or four");
+    constexpr int SUBS = 256 / THREADS;  // groups (samples in flight) per workgroup
+    constexpr uint32_t kSlots = THREADS * kPerThread;
+    constexpr uint32_t kBuckets = 2 * kSlots;
+    static_assert(kSlots <= 65536, "queue entries are 16-bit slot numbers");
+    __shared__ int32_t h_key_all[SUBS][kBuckets];     // vertex of the bucket, NULL = empty
+    __shared__ uint32_t h_claim_all[SUBS][kBuckets];  // 0 = held by a slot, else lowest proposing slot + 1
+    __shared__ uint16_t q_all[SUBS][2][kSlots];       // slots still open: this round's queue and the next's
+    __shared__ uint32_t q_fill[2];                    // queue lengths of a four-wavefront group
+    __shared__ uint32_t p_held_all[SUBS][kSlots];     // per parent: distinct vertices its slots hold
+    const uint32_t sub = threadIdx.x / (uint32_t)THREADS;
+    const uint32_t tix = threadIdx.x % (uint32_t)THREADS;  // my place in the group
+    // two half-wavefront groups share a wavefront and diverge where their samples differ
+    const uint64_t group_lanes = THREADS == 32 ? 0xFFFFFFFFull << (threadIdx.x & 32u) : ~0ull;
+    int32_t* h_key = h_key_all[sub];
+    uint32_t* h_claim = h_claim_all[sub];
+    uint32_t* p_held = p_held_all[sub];
     const uint32_t W = a.W;
-    int32_t* out_row = a.out + (uint64_t)s * W;
     uint32_t buckets = 64;                  // power of two, at least 2 W
     while (buckets < 2u * W) buckets <<= 1;
     const uint32_t mask = buckets - 1u;
 
-    // round 0 was drawn by the step's ordinary kernels: every vertex in the row is a candidate
-    int32_t cand[kPerThread];               // candidate of my slot t (NULL: nothing to place)
-    int32_t held[kPerThread];               // what my slot t ends up holding
-    int32_t first[kPerThread];              // what the step's ordinary kernels left there
-    int any_candidate = 0;
-#pragma unroll
-    for (int t = 0; t < kPerThread; ++t) {
-        const uint32_t j = threadIdx.x + (uint32_t)t * (uint32_t)THREADS;
-        cand[t] = j < W ? out_row[j] : ND_NULL_VERTEX;
-        first[t] = cand[t];
-        held[t] = ND_NULL_VERTEX;
-        any_candidate |= cand[t] >= 0 ? 1 : 0;
-    }
-    if (!__syncthreads_or(any_candidate)) return;  // uniform: a sample without live parents is done
-    for (uint32_t b = threadIdx.x; b < buckets; b += (uint32_t)THREADS) {
-        h_key[b] = ND_NULL_VERTEX;
-        h_claim[b] = 0xFFFFFFFFu;
-    }
-    __syncthreads();
+    // proposes vertex c for slot j; returns the bucket of c.  The table never holds more than W
+    // distinct vertices (every proposed vertex is held by the end of its round) in at least 2 W
+    // buckets, so a free or matching bucket is found long before the probe bound.
+    auto propose = [&](int32_t c, uint32_t j) -> uint32_t {
+        uint32_t b = ((uint32_t)c * 2654435761u) & mask;
+        for (uint32_t probe = 0; probe < buckets; ++probe) {
+            const int32_t old = atomicCAS(&h_key[b], ND_NULL_VERTEX, c);
+            if (old == ND_NULL_VERTEX || old == c) break;
+            b = (b + 1u) & mask;
+        }
+        atomicMin(&h_claim[b], j + 1u);
+        return b;
+    };
 
-    for (int32_t r = 0;; ++r) {
+    for (uint32_t s = blockIdx.x * SUBS + sub; s < num_samples; s += gridDim.x * SUBS) {  // the same s in the whole group
+        int32_t* out_row = a.out + (uint64_t)s * W;
+        // ---- round 0 was drawn by the step's ordinary kernels: every vertex in the row is a candidate
+        int32_t cand[kPerThread];               // candidate of my slot t (NULL: nothing to place)
+        int any_candidate = 0;
+#pragma unroll
+        for (int t = 0; t < kPerThread; ++t) {
+            const uint32_t j = tix + (uint32_t)t * (uint32_t)THREADS;
+            cand[t] = j < W ? out_row[j] : ND_NULL_VERTEX;
+            any_candidate |= cand[t] >= 0 ? 1 : 0;
+        }
+        if (!group_or<THREADS>(any_candidate, group_lanes)) continue;  // uniform: a sample without live parents is done
+        for (uint32_t b = tix; b < buckets; b += (uint32_t)THREADS) {
+            h_key[b] = ND_NULL_VERTEX;
+            h_claim[b] = 0xFFFFFFFFu;
+        }
+        for (uint32_t pj = tix; pj < a.W_prev; pj += (uint32_t)THREADS) p_held[pj] = 0;
+        if (THREADS > 64 && tix == 0) q_fill[0] = 0;
+        group_sync<THREADS>();
         uint32_t where[kPerThread];
 #pragma unroll
         for (int t = 0; t < kPerThread; ++t) {
-            if (cand[t] < 0) continue;
-            const uint32_t j = threadIdx.x + (uint32_t)t * (uint32_t)THREADS;
-            uint32_t b = ((uint32_t)cand[t] * 2654435761u) & mask;
-            // the table never holds more than W distinct vertices (every proposed vertex is held
-            // by the end of its round) in at least 2 W buckets, so a free or matching bucket is
-            // found long before the probe bound
-            for (uint32_t probe = 0; probe < buckets; ++probe) {
-                const int32_t old = atomicCAS(&h_key[b], ND_NULL_VERTEX, cand[t]);
-                if (old == ND_NULL_VERTEX || old == cand[t]) break;
-                b = (b + 1u) & mask;
-            }
-            atomicMin(&h_claim[b], j + 1u);
-            where[t] = b;
+            where[t] = 0;
+            if (cand[t] >= 0) where[t] = propose(cand[t], tix + (uint32_t)t * (uint32_t)THREADS);
         }
-        __syncthreads();
-        int any_open = 0;
+        group_sync<THREADS>();
         bool won[kPerThread];
 #pragma unroll
-        for (int t = 0; t < kPerThread; ++t) {
-            won[t] = false;
-            if (cand[t] < 0) continue;
-            const uint32_t j = threadIdx.x + (uint32_t)t * (uint32_t)THREADS;
-            if (h_claim[where[t]] == j + 1u) {
-                held[t] = cand[t];
-                cand[t] = ND_NULL_VERTEX;   // placed
-                won[t] = true;
-            } else {
-                any_open = 1;               // draws again
-            }
-        }
-        __syncthreads();                    // every claim has been read
-        // a winner marks its bucket as held: whoever proposes that vertex later loses
-#pragma unroll
         for (int t = 0; t < kPerThread; ++t)
-            if (won[t]) h_claim[where[t]] = 0u;
-        // uniform exit: nobody left open, or the rounds are used up
-        if (!__syncthreads_or(any_open) || r + 1 >= a.rounds) break;
+            won[t] = cand[t] >= 0 && h_claim[where[t]] == tix + (uint32_t)t * (uint32_t)THREADS + 1u;
+        group_sync<THREADS>();                  // every claim has been read
+        // a winner keeps what the step's kernels wrote and marks its bucket as held: whoever proposes
+        // that vertex later loses; a loser queues for the next round
+        uint32_t cur = 0;                       // the queue being read
+        uint32_t fill = 0;                      // entries in the queue being written (group inside one wavefront)
 #pragma unroll
         for (int t = 0; t < kPerThread; ++t) {
-            if (cand[t] < 0) continue;
-            const uint32_t j = threadIdx.x + (uint32_t)t * (uint32_t)THREADS;
-            const uint32_t pj = fastdiv(j, a.div_m);
-            const int32_t v = a.parents[(uint64_t)s * a.W_prev + pj];   // live: it drew in round 0
-            const uint64_t rs = (uint64_t)g.off[v];
-            const uint32_t deg = (uint32_t)((uint64_t)g.off[v + 1] - rs);
-            const Rand4 rn = draw4(a.seed, a.sample_base + s, j, a.step, (uint32_t)(r + 1));
-            cand[t] = g.col[rs + mulhi32(rn.r0, deg)];
+            if (won[t]) {
+                h_claim[where[t]] = 0u;
+                atomicAdd(&p_held[fastdiv(tix + (uint32_t)t * (uint32_t)THREADS, a.div_m)], 1u);
+            }
+            const bool open = cand[t] >= 0 && !won[t];
+            const uint32_t at = group_reserve<THREADS>(open, group_lanes, &fill, &q_fill[0]);
+            if (open) q_all[sub][0][at] = (uint16_t)(tix + (uint32_t)t * (uint32_t)THREADS);
         }
-    }
+        if (THREADS > 64 && tix == 0) q_fill[1] = 0;
+        group_sync<THREADS>();
+        uint32_t L = THREADS > 64 ? q_fill[0] : fill;  // slots still open (uniform in the group)
+
+        // ---- later rounds: one lane per queue entry
+        for (int32_t r = 1; r < a.rounds && L > 0; ++r) {
+            uint32_t jq[kPerThread];
 #pragma unroll
-    for (int t = 0; t < kPerThread; ++t) {
-        const uint32_t j = threadIdx.x + (uint32_t)t * (uint32_t)THREADS;
-        if (j < W && held[t] != first[t]) out_row[j] = held[t];  // most slots keep their first draw
+            for (int p = 0; p < kPerThread; ++p) {
+                const uint32_t e = tix + (uint32_t)p * (uint32_t)THREADS;
+                cand[p] = ND_NULL_VERTEX;
+                where[p] = 0;
+                jq[p] = 0;
+                if (e >= L) continue;
+                const uint32_t j = q_all[sub][cur][e];
+                const uint32_t pj = fastdiv(j, a.div_m);
+                const int32_t v = a.parents[(uint64_t)s * a.W_prev + pj];  // live: it drew in round 0
+                const uint64_t rs = (uint64_t)g.off[v];
+                const uint32_t deg = (uint32_t)((uint64_t)g.off[v + 1] - rs);
+                if (p_held[pj] >= deg) {
+                    // the parent's slots already hold as many distinct vertices as its row has entries:
+                    // whatever this slot draws is held, now and in every later round
+                    out_row[j] = ND_NULL_VERTEX;
+                    continue;
+                }
+                const Rand4 rn = draw4(a.seed, a.sample_base + s, j, a.step, (uint32_t)r);
+                cand[p] = g.col[rs + mulhi32(rn.r0, deg)];
+                jq[p] = j;
+                where[p] = propose(cand[p], j);
+            }
+            group_sync<THREADS>();
+#pragma unroll
+            for (int p = 0; p < kPerThread; ++p) won[p] = cand[p] >= 0 && h_claim[where[p]] == jq[p] + 1u;
+            group_sync<THREADS>();              // every claim has been read
+            fill = 0;
+#pragma unroll
+            for (int p = 0; p < kPerThread; ++p) {
+                if (won[p]) {
+                    h_claim[where[p]] = 0u;
+                    out_row[jq[p]] = cand[p];
+                    atomicAdd(&p_held[fastdiv(jq[p], a.div_m)], 1u);
+                }
+                const bool open = cand[p] >= 0 && !won[p];
+                const uint32_t at = group_reserve<THREADS>(open, group_lanes, &fill, &q_fill[cur ^ 1u]);
+                if (open) q_all[sub][cur ^ 1u][at] = (uint16_t)jq[p];
+            }
+            if (THREADS > 64 && tix == 0) q_fill[cur] = 0;  // everybody read it two barriers ago
+            group_sync<THREADS>();
+            cur ^= 1u;
+            L = THREADS > 64 ? q_fill[cur] : fill;
+        }
+        // ---- a slot that never won a vertex of its own ends empty
+#pragma unroll
+        for (int p = 0; p < kPerThread; ++p) {
+            const uint32_t e = tix + (uint32_t)p * (uint32_t)THREADS;
+            if (e < L) out_row[q_all[sub][cur][e]] = ND_NULL_VERTEX;
+        }
+        group_sync<THREADS>();  // table and queues are rebuilt for the group's next sample
     }
 }
 
@@ -511,15 +609,20 @@ int unique_step(const Graph& gr, const UniqueArgs& a, int64_t num_samples, hipSt
     if (num_samples == 0) return ND_OK;
 #define ND_UNIQUE_LAUNCH(THREADS, PER)                                                              \
     do {                                                                                            \
+        const int subs = 256 / (THREADS);                                                           \
+        int64_t blocks = (num_samples + subs - 1) / subs;                                           \
+        const int64_t cap = (int64_t)gr.num_cus * 16;                                               \
+        if (blocks > cap) blocks = cap; /* every group walks over samples with a stride */          \
         if (gr.off64)                                                                               \
-            hipLaunchKernelGGL((unique_kernel<int64_t, THREADS, PER>), dim3((unsigned)num_samples), \
-                               dim3(THREADS), 0, stream, view_of<int64_t>(gr), a);                  \
+            hipLaunchKernelGGL((unique_kernel<int64_t, THREADS, PER>), dim3((unsigned)blocks),      \
+                               dim3(256), 0, stream, view_of<int64_t>(gr), a, (uint32_t)num_samples); \
         else                                                                                        \
-            hipLaunchKernelGGL((unique_kernel<int32_t, THREADS, PER>), dim3((unsigned)num_samples), \
-                               dim3(THREADS), 0, stream, view_of<int32_t>(gr), a);                  \
+            hipLaunchKernelGGL((unique_kernel<int32_t, THREADS, PER>), dim3((unsigned)blocks),      \
+                               dim3(256), 0, stream, view_of<int32_t>(gr), a, (uint32_t)num_samples); \
     } while (0)
-    // up to 256 slots one wavefront per sample (its barriers cost nothing), more lanes above
-    if (a.W <= 64) ND_UNIQUE_LAUNCH(64, 1);
+    // up to 256 slots at most one wavefront per sample (its barriers cost nothing), more lanes above
+    if (a.W <= 32) ND_UNIQUE_LAUNCH(32, 1);
+    else if (a.W <= 64) ND_UNIQUE_LAUNCH(64, 1);
     else if (a.W <= 128) ND_UNIQUE_LAUNCH(64, 2);
     else if (a.W <= 256) ND_UNIQUE_LAUNCH(64, 4);
     else if (a.W <= 512) ND_UNIQUE_LAUNCH(256, 2);
