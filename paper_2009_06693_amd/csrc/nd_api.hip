@@ -424,7 +424,7 @@ int nd_graph_create(nd_graph** out, int64_t V, int64_t E, const void* row_offset
     const int rc = graph_create(&g, V, E, row_offsets, offsets_are_int64 ? 1 : 0, col_indices,
                                 weights_or_null, src_is_device, (hipStream_t)hip_stream);
     if (rc != ND_OK) return rc;
-    if (layer_prepare() != ND_OK) {
+    if (layer_prepare() != ND_OK || edges_prepare() != ND_OK) {
         graph_destroy(g);
         return ND_ERR_HIP;
     }

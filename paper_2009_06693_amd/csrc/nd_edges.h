@@ -5,6 +5,9 @@
 
 namespace nd {
 
+// Once per process and device, before the first count or fill (allows the kernels' LDS size).
+int edges_prepare();
+
 size_t edges_workspace_bytes(int64_t num_samples, int32_t n_prev);
 
 // Row sizes and their exclusive scan: row_ptr receives num_samples * n_prev + 1 entries.

@@ -18,8 +18,13 @@
 // pairs are sorted once in LDS (bitonic network); the hash table maps a vertex
 // to its run in the sorted list.  A table entry is one 32-bit word (fingerprint
 // of the vertex, start and length of the run) in a table four times the number
-// of slots, so that a miss - the common case - costs little more than one LDS
-// read; a fingerprint match is confirmed against the sorted list.
+// of slots; a fingerprint match is confirmed against the sorted list.
+//
+// Nine adjacency entries in ten are of no sample vertex, and the kernel is bound by instruction
+// issue, not by the 4 bytes per entry it streams.  So an entry first tests one bit of a 65,536-bit
+// map of the sample's vertices (no loop, no divergence); the few that pass are packed, in order,
+// into a queue of the wavefront in LDS, and the table is probed by a full wavefront of queued
+// entries at a time.
 //
 // Two passes share the kernel: counting (row sizes, then a device-wide
 // exclusive scan into 64-bit row pointers) and filling.
@@ -31,9 +36,14 @@ namespace nd {
 
 namespace {
 
-constexpr int kEdgeThreads = 1024;  // two workgroups (48 KB of LDS each) fill a CU's 32 wave slots
-constexpr int kEdgeUnroll = 4;      // adjacency loads in flight per lane
+constexpr int kEdgeThreads = 1024;  // two workgroups (76 KB of LDS each) fill a CU's 32 wave slots
+constexpr int kEdgeUnroll = 4;      // adjacency loads in flight per lane and step
+constexpr uint32_t kBatch = 64 * kEdgeUnroll;  // adjacency entries a wavefront takes per step
+constexpr int kBitWords = 2048;     // the vertex map: 65,536 bits, indexed by the top 16 bits of the hash
+constexpr uint32_t kQueueCap = 64 + kBatch;    // fewer than 64 left over plus one step's entries
 constexpr int kMaxSlots = 2048;  // new vertices per sample (ND_MAX_EDGE_SLOTS)
+constexpr size_t kEdgeLdsBytes = (size_t)kMaxSlots * 8 + (size_t)4 * kMaxSlots * 4 + (size_t)kBitWords * 4 +
+                                 (size_t)(kEdgeThreads / 64) * kQueueCap * 4;
 constexpr int kScanThreads = 256;
 constexpr int kScanItems = 16;
 constexpr int kScanTile = kScanThreads * kScanItems;
@@ -58,10 +68,19 @@ constexpr uint32_t kEmpty = 0xFFFFFFFFu;
 __device__ __forceinline__ uint32_t hash_vertex(int32_t v) { return (uint32_t)v * 0x9E3779B1u; }
 __device__ __forceinline__ uint32_t fingerprint(uint32_t h) { return (h >> 9) & 0x1FFu; }
 
+// one wavefront: its LDS operations complete in order; keeps the compiler from moving them
+__device__ __forceinline__ void wave_lds_order() {
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
 template <typename OffT, bool FILL>
 __global__ __launch_bounds__(kEdgeThreads) void edges_kernel(GraphView<OffT> g, EdgeArgs a) {
-    __shared__ uint64_t s_sorted[kMaxSlots];   // (vertex << 32 | slot), ascending; ~0 = none
-    __shared__ uint32_t table[4 * kMaxSlots];  // entries as described above
+    extern __shared__ __align__(16) unsigned char s_dyn[];
+    uint64_t* s_sorted = (uint64_t*)s_dyn;                // [kMaxSlots] (vertex << 32 | slot), ascending; ~0 = none
+    uint32_t* table = (uint32_t*)(s_sorted + kMaxSlots);  // [4 * kMaxSlots] entries as described above
+    uint32_t* s_bits = table + 4 * kMaxSlots;             // [kBitWords] bit set: some sample vertex hashes here
+    int32_t* s_queue = (int32_t*)(s_bits + kBitWords);    // per wavefront: entries that passed the bit test
     const uint32_t b = blockIdx.x;
     const uint32_t tid = threadIdx.x;
     const uint32_t mask = 4u * a.m2 - 1u;
@@ -81,6 +100,7 @@ __global__ __launch_bounds__(kEdgeThreads) void edges_kernel(GraphView<OffT> g, 
         s_sorted[i] = key;
     }
     for (uint32_t i = tid; i < 4u * a.m2; i += kEdgeThreads) table[i] = kEmpty;
+    for (uint32_t i = tid; i < (uint32_t)kBitWords; i += kEdgeThreads) s_bits[i] = 0u;
     __syncthreads();
 
     // bitonic sorting network over m2 keys
@@ -118,78 +138,242 @@ __global__ __launch_bounds__(kEdgeThreads) void edges_kernel(GraphView<OffT> g, 
         const uint32_t entry = (fingerprint(h) << 23) | ((lo - k) << 11) | k;
         uint32_t pos = h >> a.hash_shift;
         while (atomicCAS(&table[pos], kEmpty, entry) != kEmpty) pos = (pos + 1u) & mask;
+        atomicOr(&s_bits[h >> 21], 1u << ((h >> 16) & 31u));
     }
     __syncthreads();
 
+    // ---- the wavefronts stream the adjacency lists of the sample's transits, a row at a time each.
+    // Everything about a row is the same in all lanes of its wavefront and is kept in scalar
+    // registers.  The loop runs over steps of up to kBatch entries of a row; the entries of the next
+    // step (the same row's or the next row's) are requested before the current step is worked on,
+    // and so are, one and two rows ahead, the offsets and the transit of the rows to come.
+    constexpr uint32_t kStride = kEdgeThreads / 64;
     const int lane = lane_id();
-    for (uint32_t t = wave_id(); t < a.n_prev; t += kEdgeThreads / 64) {
-        const uint64_t row = (uint64_t)b * a.n_prev + t;
-        int32_t tv = a.transits[row];
-        if (tv >= g.V || tv < ND_NULL_VERTEX) {
+    const uint32_t wave = wave_uniform((uint32_t)wave_id());
+    int32_t* queue = s_queue + wave * kQueueCap;
+    const uint64_t row0 = (uint64_t)b * a.n_prev;
+
+    auto transit_of = [&](uint32_t row) -> int32_t {  // as stored; NULL beyond the last row
+        return row < a.n_prev ? a.transits[row0 + row] : ND_NULL_VERTEX;
+    };
+    auto checked = [&](int32_t v) -> int32_t {
+        v = wave_uniform(v);
+        if (v >= g.V || v < ND_NULL_VERTEX) {
             bad = true;
-            tv = ND_NULL_VERTEX;
+            v = ND_NULL_VERTEX;
         }
-        uint32_t count = 0;
-        int64_t wbase = 0;
-        if constexpr (FILL) wbase = a.row_ptr[row];
-        if (tv >= 0) {
-            const uint64_t rs = (uint64_t)g.off[tv];
-            const uint64_t deg = (uint64_t)g.off[tv + 1] - rs;
-            for (uint64_t e0 = 0; e0 < deg; e0 += 64 * kEdgeUnroll) {
-                int32_t u[kEdgeUnroll];
-#pragma unroll
-                for (int r = 0; r < kEdgeUnroll; ++r) {  // all loads first: the loop is latency bound
-                    const uint64_t e = e0 + (uint64_t)r * 64 + lane;
-                    u[r] = e < deg ? g.col[rs + e] : ND_NULL_VERTEX;
-                }
-#pragma unroll
-                for (int r = 0; r < kEdgeUnroll; ++r) {
-                    uint32_t c = 0, k = 0;
-                    if (u[r] >= 0) {
-                        const uint32_t h = hash_vertex(u[r]);
-                        const uint32_t fp = fingerprint(h);
-                        uint32_t pos = h >> a.hash_shift;
-                        uint32_t en;
-                        while ((en = table[pos]) != kEmpty) {  // ends: the table is never full
-                            if ((en >> 23) == fp && (int32_t)(s_sorted[en & 0x7FFu] >> 32) == u[r]) {
-                                k = en & 0x7FFu;
-                                c = (en >> 11) & 0xFFFu;
-                                break;
-                            }
-                            pos = (pos + 1u) & mask;
-                        }
-                    }
-                    if constexpr (FILL) {
-                        if (e0 + (uint64_t)r * 64 < deg) {  // same for the whole wavefront
-                            // the 64 lanes hold runs (k, c); their entries are written in lane order,
-                            // 64 at a time, each output position finding its lane by a search over
-                            // the running sums
-                            const uint32_t incl = wave_inclusive_scan(c, lane);
-                            const uint32_t total = __shfl(incl, 63, 64);
-                            const uint32_t ex = incl - c;
-                            for (uint32_t base = 0; base < total; base += 64) {
-                                const uint32_t p = base + lane;
-                                uint32_t owner = 0;
-#pragma unroll
-                                for (uint32_t step = 32; step > 0; step >>= 1)
-                                    if (__shfl(incl, (int)(owner + step - 1), 64) <= p) owner += step;
-                                owner &= 63u;
-                                const uint32_t ok = __shfl(k, (int)owner, 64);
-                                const uint32_t oex = __shfl(ex, (int)owner, 64);
-                                if (p < total && wbase + p < a.capacity)
-                                    a.edge_slot[wbase + p] = (int32_t)(uint32_t)s_sorted[ok + (p - oex)];
-                            }
-                            wbase += total;
-                        }
-                    } else {
-                        count += c;
-                    }
-                }
+        return v;
+    };
+    // the row whose entries are being requested
+    uint32_t t = wave;
+    uint64_t rs = 0, deg = 0;   // where its adjacency list starts and how long it is (0: nothing to stream)
+    uint64_t e0 = 0;            // the next entry of it to request
+    int64_t wb = 0;             // FILL: where its output starts
+    // one row ahead: transit known, offsets (FILL: row pointers) requested; two ahead: transit requested
+    int32_t tv_a = ND_NULL_VERTEX, tv_b = ND_NULL_VERTEX;
+    OffT off_a0 = 0, off_a1 = 0;
+    int64_t rp_a0 = 0, rp_a1 = 0;
+    auto request_a = [&]() {
+        off_a0 = off_a1 = 0;
+        if (tv_a >= 0) {
+            off_a0 = g.off[tv_a];
+            off_a1 = g.off[tv_a + 1];
+        }
+        if constexpr (FILL) {
+            rp_a0 = rp_a1 = 0;
+            if (t + kStride < a.n_prev) {
+                rp_a0 = a.row_ptr[row0 + t + kStride];
+                rp_a1 = a.row_ptr[row0 + t + kStride + 1];
             }
         }
-        if constexpr (!FILL) {
-            const uint32_t incl = wave_inclusive_scan(count, lane);
-            if (lane == 63) a.counts[row] = (int32_t)incl;
+    };
+    auto advance = [&]() {
+        t += kStride;
+        rs = wave_uniform((uint64_t)off_a0);
+        deg = wave_uniform((uint64_t)off_a1) - rs;
+        if constexpr (FILL) {
+            wb = wave_uniform(rp_a0);
+            if (wave_uniform(rp_a1) == wb) deg = 0;  // the counting pass found nothing in this row
+        }
+        e0 = 0;
+        tv_a = checked(tv_b);
+        request_a();
+        tv_b = transit_of(t + 2 * kStride);
+    };
+    auto skip_empty_rows = [&]() {
+        while (t < a.n_prev && deg == 0) {
+            if constexpr (!FILL)
+                if (lane == 0) a.counts[row0 + t] = 0;
+            advance();
+        }
+    };
+    auto request_entries = [&](int32_t (&u)[kEdgeUnroll]) {
+        const int32_t* p = g.col + rs + e0;
+        const uint64_t left = deg - e0;
+        const uint32_t cnt = left < kBatch ? (uint32_t)left : kBatch;
+        if (cnt == kBatch) {  // a full step, the common case: nothing to test
+#pragma unroll
+            for (int r = 0; r < kEdgeUnroll; ++r) u[r] = p[r * 64 + lane];
+            return;
+        }
+#pragma unroll
+        for (int r = 0; r < kEdgeUnroll; ++r) {
+            u[r] = ND_NULL_VERTEX;
+            // the test is the same in all lanes; inside the last 64 entries a lane past the end
+            // reads the last entry again instead of branching (and drops it when it looks at it:
+            // looking at it here would wait for each load in turn)
+            if ((uint32_t)r * 64u < cnt) {
+                const uint32_t e = (uint32_t)r * 64u + (uint32_t)lane;
+                u[r] = p[e < cnt ? e : cnt - 1u];
+            }
+        }
+    };
+
+    {   // the pipeline's first row is loaded directly
+        const int32_t tv = checked(transit_of(t));
+        if (tv >= 0) {
+            rs = wave_uniform((uint64_t)g.off[tv]);
+            deg = wave_uniform((uint64_t)g.off[tv + 1]) - rs;
+        }
+        if constexpr (FILL) {
+            if (t < a.n_prev) {
+                wb = wave_uniform(a.row_ptr[row0 + t]);
+                if (wave_uniform(a.row_ptr[row0 + t + 1]) == wb) deg = 0;
+            }
+        }
+        tv_a = checked(transit_of(t + kStride));
+        request_a();
+        tv_b = transit_of(t + 2 * kStride);
+    }
+    skip_empty_rows();
+    int32_t u_next[kEdgeUnroll];
+#pragma unroll
+    for (int r = 0; r < kEdgeUnroll; ++r) u_next[r] = 0;
+    if (t < a.n_prev) request_entries(u_next);
+
+    uint32_t queued = 0;  // entries in the queue (the same in all lanes)
+    uint32_t count = 0;   // counting pass: my share of the row's edges
+    int64_t wbase = wb;   // filling pass: where the row's next edge goes
+    while (t < a.n_prev) {
+        // ---- the step whose entries have been requested
+        int32_t u[kEdgeUnroll];
+#pragma unroll
+        for (int r = 0; r < kEdgeUnroll; ++r) {
+            u[r] = u_next[r];
+            // taken here, before the requests below are issued: loads return in order, and a wait
+            // for these entries placed after those requests would wait for them as well
+            asm volatile("" : "+v"(u[r]));
+        }
+        const uint64_t left = deg - e0;
+        const uint32_t cnt = left < kBatch ? (uint32_t)left : kBatch;
+        const bool row_ends = left <= kBatch;
+        const uint32_t t_now = t;
+        // ---- request the next step's entries before working on this one
+        if (row_ends) {
+            advance();
+            skip_empty_rows();
+        } else {
+            e0 += kBatch;
+        }
+        if (t < a.n_prev) request_entries(u_next);
+
+        // ---- entries that pass the bit test join the queue, in order
+#pragma unroll
+        for (int r = 0; r < kEdgeUnroll; ++r) {
+            if (cnt != kBatch && (uint32_t)r * 64u >= cnt) break;  // the same for the whole wavefront
+            const uint32_t h = hash_vertex(u[r]);
+            bool pass = ((s_bits[h >> 21] >> ((h >> 16) & 31u)) & 1u) != 0u;
+            if (cnt != kBatch) pass = pass && (uint32_t)r * 64u + (uint32_t)lane < cnt;
+            const uint64_t votes = __ballot(pass);
+            const uint32_t ahead = __builtin_amdgcn_mbcnt_hi((uint32_t)(votes >> 32),
+                                                             __builtin_amdgcn_mbcnt_lo((uint32_t)votes, 0u));
+            if (pass) queue[queued + ahead] = u[r];
+            queued += (uint32_t)__popcll(votes);
+        }
+        wave_lds_order();
+
+        // ---- the table is probed by 64 queued entries at a time (by what is left when the row ends)
+        uint32_t head = 0;
+        while (queued - head >= 64u || (row_ends && head < queued)) {
+            const uint32_t n = queued - head < 64u ? queued - head : 64u;
+            const int32_t v = (uint32_t)lane < n ? queue[head + lane] : ND_NULL_VERTEX;
+            uint32_t c = 0, k = 0;
+            if (v >= 0) {
+                const uint32_t h = hash_vertex(v);
+                const uint32_t fp = fingerprint(h);
+                uint32_t pos = h >> a.hash_shift;
+                uint32_t en;
+                while ((en = table[pos]) != kEmpty) {  // ends: the table is never full
+                    if ((en >> 23) == fp && (int32_t)(s_sorted[en & 0x7FFu] >> 32) == v) {
+                        k = en & 0x7FFu;
+                        c = (en >> 11) & 0xFFFu;
+                        break;
+                    }
+                    pos = (pos + 1u) & mask;
+                }
+            }
+            if constexpr (FILL) {
+                // the lanes hold runs (k, c), most of them empty or one entry long.  A lane's first
+                // entry goes to the number of non-empty lanes below it plus what the few longer
+                // runs below it add; those are walked one by one (the loop is the same in all lanes).
+                const uint64_t writers = __ballot(c >= 1u);
+                uint32_t first = __builtin_amdgcn_mbcnt_hi((uint32_t)(writers >> 32),
+                                                        __builtin_amdgcn_mbcnt_lo((uint32_t)writers, 0u));
+                uint32_t sum = (uint32_t)__popcll(writers), longest = 1;
+                for (uint64_t rest = __ballot(c > 1u); rest != 0ull; rest &= rest - 1ull) {
+                    const int at = __builtin_ctzll(rest);
+                    const uint32_t more = (uint32_t)__builtin_amdgcn_readlane((int)c, at) - 1u;
+                    if (lane > at) first += more;
+                    sum += more;
+                    longest = more + 1u > longest ? more + 1u : longest;
+                }
+                if (longest <= 8u) {
+                    for (uint32_t i = 0; i < longest; ++i)
+                        if (i < c && wbase + first + i < a.capacity)
+                            a.edge_slot[wbase + first + i] = (int32_t)(uint32_t)s_sorted[k + i];
+                    wbase += sum;
+                    head += n;
+                    continue;
+                }
+                // a vertex held by many slots: the entries are written in lane order, 64 at a
+                // time, each output position finding its lane by a search over the running sums
+                const uint32_t incl = wave_inclusive_scan(c, lane);
+                const uint32_t total = wave_uniform((uint32_t)__shfl(incl, 63, 64));
+                const uint32_t ex = incl - c;
+                for (uint32_t base = 0; base < total; base += 64) {
+                    const uint32_t p = base + lane;
+                    uint32_t owner = 0;
+#pragma unroll
+                    for (uint32_t step = 32; step > 0; step >>= 1)
+                        if (__shfl(incl, (int)(owner + step - 1), 64) <= p) owner += step;
+                    owner &= 63u;
+                    const uint32_t ok = __shfl(k, (int)owner, 64);
+                    const uint32_t oex = __shfl(ex, (int)owner, 64);
+                    if (p < total && wbase + p < a.capacity)
+                        a.edge_slot[wbase + p] = (int32_t)(uint32_t)s_sorted[ok + (p - oex)];
+                }
+                wbase += total;
+            } else {
+                count += c;
+            }
+            head += n;
+        }
+        if (row_ends) {
+            if constexpr (!FILL) {
+                const uint32_t incl = wave_inclusive_scan(count, lane);
+                if (lane == 63) a.counts[row0 + t_now] = (int32_t)incl;
+                count = 0;
+            }
+            queued = 0;
+            wbase = wb;  // of the row the next step belongs to
+            wave_lds_order();
+        } else if (head > 0u) {  // fewer than 64 are left: they move to the front
+            const uint32_t rest = queued - head;
+            const int32_t moved = (uint32_t)lane < rest ? queue[head + lane] : 0;
+            wave_lds_order();
+            if ((uint32_t)lane < rest) queue[lane] = moved;
+            queued = rest;
+            wave_lds_order();
         }
     }
     if (bad && a.status) atomicOr(a.status, 1u);
@@ -272,6 +456,20 @@ inline EdgeArgs make_args(const int32_t* transits, int32_t n_prev, const int32_t
 
 }  // namespace
 
+// Dynamic LDS above the 64 KB default has to be allowed once per kernel; done when a graph is
+// created so that the entry points themselves only launch.
+int edges_prepare() {
+#define ND_EDGES_ALLOW(OFFT, FILL)                                                              \
+    ND_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(&edges_kernel<OFFT, FILL>),  \
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)kEdgeLdsBytes))
+    ND_EDGES_ALLOW(int64_t, true);
+    ND_EDGES_ALLOW(int64_t, false);
+    ND_EDGES_ALLOW(int32_t, true);
+    ND_EDGES_ALLOW(int32_t, false);
+#undef ND_EDGES_ALLOW
+    return ND_OK;
+}
+
 size_t edges_workspace_bytes(int64_t num_samples, int32_t n_prev) {
     const int64_t rows = num_samples * (int64_t)n_prev;
     const size_t counts = ((size_t)(rows > 0 ? rows : 1) * 4 + 255) / 256 * 256;
@@ -294,10 +492,10 @@ int edges_count(const Graph& gr, const int32_t* transits, int32_t n_prev, const 
         a.status = status;
         if (gr.off64)
             hipLaunchKernelGGL((edges_kernel<int64_t, false>), dim3((unsigned)num_samples),
-                               dim3(kEdgeThreads), 0, stream, view_of<int64_t>(gr), a);
+                               dim3(kEdgeThreads), kEdgeLdsBytes, stream, view_of<int64_t>(gr), a);
         else
             hipLaunchKernelGGL((edges_kernel<int32_t, false>), dim3((unsigned)num_samples),
-                               dim3(kEdgeThreads), 0, stream, view_of<int32_t>(gr), a);
+                               dim3(kEdgeThreads), kEdgeLdsBytes, stream, view_of<int32_t>(gr), a);
         hipLaunchKernelGGL(scan_sums_kernel, dim3((unsigned)tiles), dim3(kScanThreads), 0, stream, counts,
                            rows, sums);
     }
@@ -319,10 +517,10 @@ int edges_fill(const Graph& gr, const int32_t* transits, int32_t n_prev, const i
     a.status = nullptr;
     if (gr.off64)
         hipLaunchKernelGGL((edges_kernel<int64_t, true>), dim3((unsigned)num_samples), dim3(kEdgeThreads),
-                           0, stream, view_of<int64_t>(gr), a);
+                           kEdgeLdsBytes, stream, view_of<int64_t>(gr), a);
     else
         hipLaunchKernelGGL((edges_kernel<int32_t, true>), dim3((unsigned)num_samples), dim3(kEdgeThreads),
-                           0, stream, view_of<int32_t>(gr), a);
+                           kEdgeLdsBytes, stream, view_of<int32_t>(gr), a);
     ND_HIP_CHECK(hipGetLastError());
     return ND_OK;
 }

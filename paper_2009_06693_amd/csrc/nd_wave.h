@@ -11,6 +11,18 @@ __device__ __forceinline__ int wave_id() { return (int)(threadIdx.x >> 6); }
 
 __device__ __forceinline__ uint64_t lanes_below(int lane) { return (1ull << lane) - 1ull; }
 
+// A value that is the same in every lane of the wavefront, moved to scalar registers: the compiler
+// cannot see that (threadIdx.x >> 6 and whatever is loaded through it look divergent), and loops
+// and branches on such a value would otherwise run on execution masks instead of scalar branches.
+__device__ __forceinline__ uint32_t wave_uniform(uint32_t x) {
+    return (uint32_t)__builtin_amdgcn_readfirstlane((int)x);
+}
+__device__ __forceinline__ int32_t wave_uniform(int32_t x) { return __builtin_amdgcn_readfirstlane(x); }
+__device__ __forceinline__ uint64_t wave_uniform(uint64_t x) {
+    return ((uint64_t)wave_uniform((uint32_t)(x >> 32)) << 32) | wave_uniform((uint32_t)x);
+}
+__device__ __forceinline__ int64_t wave_uniform(int64_t x) { return (int64_t)wave_uniform((uint64_t)x); }
+
 // Inclusive scan across the 64 lanes of a wavefront.
 template <typename T>
 __device__ __forceinline__ T wave_inclusive_scan(T x, int lane) {
