@@ -72,6 +72,25 @@ def test_every_vertex_once_reads_back_the_adjacency_rows():
     assert np.array_equal(slots.cpu().numpy(), g.col_indices)
 
 
+@pytest.mark.parametrize("copies", [2, 9, 70, 2048])
+def test_a_vertex_held_by_many_slots_gives_one_edge_per_slot(copies):
+    """Runs of equal vertices of every length class: written lane by lane up to 8, by the search over
+    running sums above, and more than one 64-wide group of outputs per queue drain at 70 and 2,048."""
+    g = _small
+    deg = np.diff(g.row_offsets)
+    hub = int(np.argmax(deg))
+    nbrs = g.col_indices[g.row_offsets[hub]:g.row_offsets[hub + 1]]
+    m = 2048
+    rng = np.random.default_rng(copies)
+    sampled = rng.integers(0, g.V, (2, m)).astype(np.int32)
+    sampled[0, rng.choice(m, copies, replace=False)] = nbrs[0]          # one neighbour of the hub, many times
+    sampled[1, :] = nbrs[rng.integers(0, nbrs.size, m)] if copies == 2048 else sampled[1]
+    transits = np.full((2, 40), hub, dtype=np.int32)
+    transits[:, 1::2] = rng.integers(0, g.V, (2, 20))
+    ptr = _compare(g, transits, sampled)
+    assert ptr[1] - ptr[0] >= copies
+
+
 def test_empty_and_error_cases():
     g = _small
     dg, _ = device_graph(g)
