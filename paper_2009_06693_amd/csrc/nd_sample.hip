@@ -300,7 +300,7 @@ __global__ __launch_bounds__(kWgThreads) void sample_tp_kernel(
         for (;;) {
             if (threadIdx.x == 0) s_item = atomicAdd(&ctl->wg_cursor, 1u);
             __syncthreads();
-            const uint32_t i = s_item;
+            const uint32_t i = wave_uniform(s_item);  // the item's description stays in scalar registers
             if (i >= n_items) break;  // uniform: every wave of the workgroup leaves here
             const bool grid = i >= n_wg;
             const uint32_t gid = (uint32_t)(grid ? chunk_gid[i - n_wg] : list_wg[i]);

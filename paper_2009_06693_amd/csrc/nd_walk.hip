@@ -158,7 +158,7 @@ __global__ __launch_bounds__(THREADS) void walk_window_kernel(GraphView<OffT> g,
 
         // ---- 1. transit enumeration: every live slot enters its transit in the window's table
         uint32_t bucket[ITEMS];
-        uint32_t n_first = 0, n_live = 0;
+        uint32_t first_w = 0, live_w = 0;  // of my wavefront: transits entered first, live slots
 #pragma unroll
         for (int it = 0; it < ITEMS; ++it) {
             const uint32_t l = (uint32_t)(it * THREADS + tid);
@@ -171,15 +171,15 @@ __global__ __launch_bounds__(THREADS) void walk_window_kernel(GraphView<OffT> g,
                 }
             }
             bucket[it] = 0;
+            bool entered = false;
             if (cur[it] >= 0) {
-                ++n_live;
                 const uint32_t key = (uint32_t)cur[it];
                 uint32_t b = (key * 2654435761u) >> 7 & (NB - 1u);
                 for (uint32_t probe = 0; probe < NB; ++probe) {  // the table is at most half full
                     const unsigned long long old = s_tab[b];
                     if (tab_tag(old) != si + 1u) {                // free: claim it with count 1
                         if (atomicCAS(&s_tab[b], old, tag | (1ull << 32) | key) == old) {
-                            ++n_first;
+                            entered = true;
                             break;
                         }
                         continue;                                 // somebody else took it: look again
@@ -192,9 +192,10 @@ __global__ __launch_bounds__(THREADS) void walk_window_kernel(GraphView<OffT> g,
                 }
                 bucket[it] = b;
             }
+            first_w += (uint32_t)__popcll(__ballot(entered));
+            live_w += (uint32_t)__popcll(__ballot(cur[it] >= 0));
         }
         {   // counters of the step (one LDS atomic per wave)
-            const uint32_t first_w = wave_inclusive_scan(n_first, lane), live_w = wave_inclusive_scan(n_live, lane);
             if (lane == 63) {
                 if (first_w) atomicAdd(&cnt_now[2], first_w);
                 if (live_w) atomicAdd(&cnt_now[1], live_w);
@@ -241,7 +242,7 @@ __global__ __launch_bounds__(THREADS) void walk_window_kernel(GraphView<OffT> g,
             }
         }
         __syncthreads();
-        const uint32_t P = cnt_now[0];  // pairs to group
+        const uint32_t P = wave_uniform(cnt_now[0]);  // pairs to group
 
         if (P > 0) {  // uniform for the workgroup
             // ---- 3. stable LSD radix sort of the P pairs by transit
@@ -342,7 +343,7 @@ __global__ __launch_bounds__(THREADS) void walk_window_kernel(GraphView<OffT> g,
                 }
                 __syncthreads();
             }
-            const uint32_t n_heavy = cnt_now[3];
+            const uint32_t n_heavy = wave_uniform(cnt_now[3]);
             uint32_t n_staged = 0, heavy_draws = 0;
             for (uint32_t hi = 0; hi < n_heavy; ++hi) {  // uniform trip count
                 const uint32_t p0 = heavy_list[hi];
