@@ -313,33 +313,22 @@ __global__ __launch_bounds__(kEdgeThreads) void edges_kernel(GraphView<OffT> g, 
                 }
             }
             if constexpr (FILL) {
-                // the lanes hold runs (k, c), most of them empty or one entry long.  A lane's first
-                // entry goes to the number of non-empty lanes below it plus what the few longer
-                // runs below it add; those are walked one by one (the loop is the same in all lanes).
-                const uint64_t writers = __ballot(c >= 1u);
-                uint32_t first = __builtin_amdgcn_mbcnt_hi((uint32_t)(writers >> 32),
-                                                        __builtin_amdgcn_mbcnt_lo((uint32_t)writers, 0u));
-                uint32_t sum = (uint32_t)__popcll(writers), longest = 1;
-                for (uint64_t rest = __ballot(c > 1u); rest != 0ull; rest &= rest - 1ull) {
-                    const int at = __builtin_ctzll(rest);
-                    const uint32_t more = (uint32_t)__builtin_amdgcn_readlane((int)c, at) - 1u;
-                    if (lane > at) first += more;
-                    sum += more;
-                    longest = more + 1u > longest ? more + 1u : longest;
-                }
-                if (longest <= 8u) {
-                    for (uint32_t i = 0; i < longest; ++i)
-                        if (i < c && wbase + first + i < a.capacity)
-                            a.edge_slot[wbase + first + i] = (int32_t)(uint32_t)s_sorted[k + i];
-                    wbase += sum;
+                // the lanes hold runs (k, c), most of them empty or one entry long: a lane writes
+                // its run entry by entry from the running sum of the lanes below it (the loop is
+                // the same in all lanes and ends with the longest run)
+                const uint32_t incl = wave_inclusive_scan(c, lane);
+                const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+                const uint32_t ex = incl - c;
+                if (__ballot(c > 8u) == 0ull) {
+                    for (uint32_t i = 0; __ballot(i < c) != 0ull; ++i)
+                        if (i < c && wbase + ex + i < a.capacity)
+                            a.edge_slot[wbase + ex + i] = (int32_t)(uint32_t)s_sorted[k + i];
+                    wbase += total;
                     head += n;
                     continue;
                 }
                 // a vertex held by many slots: the entries are written in lane order, 64 at a
                 // time, each output position finding its lane by a search over the running sums
-                const uint32_t incl = wave_inclusive_scan(c, lane);
-                const uint32_t total = wave_uniform((uint32_t)__shfl(incl, 63, 64));
-                const uint32_t ex = incl - c;
                 for (uint32_t base = 0; base < total; base += 64) {
                     const uint32_t p = base + lane;
                     uint32_t owner = 0;

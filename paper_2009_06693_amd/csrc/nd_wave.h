@@ -23,7 +23,24 @@ __device__ __forceinline__ uint64_t wave_uniform(uint64_t x) {
 }
 __device__ __forceinline__ int64_t wave_uniform(int64_t x) { return (int64_t)wave_uniform((uint64_t)x); }
 
-// Inclusive scan across the 64 lanes of a wavefront.
+// Inclusive sum across the 64 lanes of a wavefront for 32-bit values, in six DPP additions: four
+// shifts inside the rows of 16 lanes (a lane outside the row contributes 0), then lane 15 of rows
+// 0 and 2 into rows 1 and 3, then lane 31 into rows 2 and 3.  Every lane must be active.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_moved(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xf, true);
+}
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v, int /*lane*/) {
+    v += dpp_moved<0x111, 0xf>(v);  // row_shr:1
+    v += dpp_moved<0x112, 0xf>(v);  // row_shr:2
+    v += dpp_moved<0x114, 0xf>(v);  // row_shr:4
+    v += dpp_moved<0x118, 0xf>(v);  // row_shr:8
+    v += dpp_moved<0x142, 0xa>(v);  // row_bcast:15 into rows 1 and 3
+    v += dpp_moved<0x143, 0xc>(v);  // row_bcast:31 into rows 2 and 3
+    return v;
+}
+
+// Inclusive scan across the 64 lanes of a wavefront (any type, through shuffles).
 template <typename T>
 __device__ __forceinline__ T wave_inclusive_scan(T x, int lane) {
 #pragma unroll
