@@ -95,7 +95,6 @@ __global__ __launch_bounds__(THREADS) void upsweep_kernel(
         }
     }
     if (FIRST && base < n) {
-#pragma unroll 4
         for (int i = tid; i < kTile; i += THREADS) {
             const int64_t idx = base + i;  // a wavefront covers 64 consecutive slots
             int32_t k = ND_NULL_VERTEX;
