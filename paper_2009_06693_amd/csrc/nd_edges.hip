@@ -28,6 +28,8 @@
 //
 // Two passes share the kernel: counting (row sizes, then a device-wide
 // exclusive scan into 64-bit row pointers) and filling.
+#include <type_traits>
+
 #include "nd_common.h"
 #include "nd_edges.h"
 #include "nd_wave.h"
@@ -39,7 +41,7 @@ namespace {
 constexpr int kEdgeThreads = 1024;  // two workgroups (76 KB of LDS each) fill a CU's 32 wave slots
 constexpr int kEdgeUnroll = 4;      // adjacency loads in flight per lane and step
 constexpr uint32_t kBatch = 64 * kEdgeUnroll;  // adjacency entries a wavefront takes per step
-constexpr int kBitWords = 2048;     // the vertex map: 65,536 bits, indexed by the top 16 bits of the hash
+constexpr int kBitWords = 2048;     // the vertex map: 65,536 bits, indexed by the vertex id folded to 16 bits
 constexpr uint32_t kQueueCap = 64 + kBatch;    // fewer than 64 left over plus one step's entries
 constexpr int kMaxSlots = 2048;  // new vertices per sample (ND_MAX_EDGE_SLOTS)
 constexpr size_t kEdgeLdsBytes = (size_t)kMaxSlots * 8 + (size_t)4 * kMaxSlots * 4 + (size_t)kBitWords * 4 +
@@ -67,6 +69,10 @@ struct EdgeArgs {
 constexpr uint32_t kEmpty = 0xFFFFFFFFu;
 __device__ __forceinline__ uint32_t hash_vertex(int32_t v) { return (uint32_t)v * 0x9E3779B1u; }
 __device__ __forceinline__ uint32_t fingerprint(uint32_t h) { return (h >> 9) & 0x1FFu; }
+// The vertex's bit in the 65,536-bit map: the id folded to 16 bits.  Two shifts and an exclusive or,
+// where the multiplicative hash costs a quarter-rate multiply per adjacency entry, and neighbouring
+// ids - an ascending adjacency list is full of them - read the same or neighbouring words of LDS.
+__device__ __forceinline__ uint32_t map_bit(int32_t v) { return ((uint32_t)v ^ ((uint32_t)v >> 16)) & 0xFFFFu; }
 
 // one wavefront: its LDS operations complete in order; keeps the compiler from moving them
 __device__ __forceinline__ void wave_lds_order() {
@@ -138,7 +144,8 @@ __global__ __launch_bounds__(kEdgeThreads) void edges_kernel(GraphView<OffT> g, 
         const uint32_t entry = (fingerprint(h) << 23) | ((lo - k) << 11) | k;
         uint32_t pos = h >> a.hash_shift;
         while (atomicCAS(&table[pos], kEmpty, entry) != kEmpty) pos = (pos + 1u) & mask;
-        atomicOr(&s_bits[h >> 21], 1u << ((h >> 16) & 31u));
+        const uint32_t bi = map_bit(v);
+        atomicOr(&s_bits[bi >> 5], 1u << (bi & 31u));
     }
     __syncthreads();
 
@@ -277,19 +284,26 @@ __global__ __launch_bounds__(kEdgeThreads) void edges_kernel(GraphView<OffT> g, 
         }
         if (t < a.n_prev) request_entries(u_next);
 
-        // ---- entries that pass the bit test join the queue, in order
+        // ---- entries that pass the bit test join the queue, in order.  Two copies of the code: a
+        // full step (the common case) tests nothing but the bit.
+        auto enqueue = [&](auto full_step) {
+            constexpr bool kFull = decltype(full_step)::value;
 #pragma unroll
-        for (int r = 0; r < kEdgeUnroll; ++r) {
-            if (cnt != kBatch && (uint32_t)r * 64u >= cnt) break;  // the same for the whole wavefront
-            const uint32_t h = hash_vertex(u[r]);
-            bool pass = ((s_bits[h >> 21] >> ((h >> 16) & 31u)) & 1u) != 0u;
-            if (cnt != kBatch) pass = pass && (uint32_t)r * 64u + (uint32_t)lane < cnt;
-            const uint64_t votes = __ballot(pass);
-            const uint32_t ahead = __builtin_amdgcn_mbcnt_hi((uint32_t)(votes >> 32),
-                                                             __builtin_amdgcn_mbcnt_lo((uint32_t)votes, 0u));
-            if (pass) queue[queued + ahead] = u[r];
-            queued += (uint32_t)__popcll(votes);
-        }
+            for (int r = 0; r < kEdgeUnroll; ++r) {
+                if (!kFull && (uint32_t)r * 64u >= cnt) break;  // the same for the whole wavefront
+                const uint32_t bi = map_bit(u[r]);
+                bool pass = ((s_bits[bi >> 5] >> (bi & 31u)) & 1u) != 0u;
+                if (!kFull) pass = pass && (uint32_t)r * 64u + (uint32_t)lane < cnt;
+                const uint64_t votes = __ballot(pass);
+                const uint32_t ahead = __builtin_amdgcn_mbcnt_hi((uint32_t)(votes >> 32),
+                                                                 __builtin_amdgcn_mbcnt_lo((uint32_t)votes, 0u));
+                // no branch: a lane that does not pass writes to the queue's spare last place
+                queue[pass ? queued + ahead : kQueueCap - 1u] = u[r];
+                queued += (uint32_t)__popcll(votes);
+            }
+        };
+        if (cnt == kBatch) enqueue(std::true_type{});
+        else enqueue(std::false_type{});
         wave_lds_order();
 
         // ---- the table is probed by 64 queued entries at a time (by what is left when the row ends)
