@@ -165,6 +165,33 @@ __global__ __launch_bounds__(kBinscanThreads) void binscan_kernel(uint32_t* __re
     if (threadIdx.x == 0) bin_total[blockIdx.x] = carry;
 }
 
+// The lanes of the wavefront that hold digit d (among the lanes of `candidates`): one ballot per
+// digit bit, the bit spread over the lane's word so that "my bit equals theirs" is one XNOR per half.
+template <int BITS>
+__device__ __forceinline__ uint64_t digit_peers_fixed(uint32_t d, uint64_t candidates) {
+    uint32_t lo = (uint32_t)candidates, hi = (uint32_t)(candidates >> 32);
+#pragma unroll
+    for (int b = 0; b < BITS; ++b) {
+        const uint32_t mine = (uint32_t)__builtin_amdgcn_sbfe((int)d, (uint32_t)b, 1u);  // all ones or zero
+        const uint64_t theirs = __ballot(mine != 0u);
+        lo &= ~((uint32_t)theirs ^ mine);
+        hi &= ~((uint32_t)(theirs >> 32) ^ mine);
+    }
+    return ((uint64_t)hi << 32) | lo;
+}
+__device__ __forceinline__ uint64_t digit_peers(uint32_t d, uint64_t candidates, int bits) {
+    switch (bits) {  // the same for the whole launch
+        case 8: return digit_peers_fixed<8>(d, candidates);
+        case 7: return digit_peers_fixed<7>(d, candidates);
+        case 6: return digit_peers_fixed<6>(d, candidates);
+        case 5: return digit_peers_fixed<5>(d, candidates);
+        case 4: return digit_peers_fixed<4>(d, candidates);
+        case 3: return digit_peers_fixed<3>(d, candidates);
+        case 2: return digit_peers_fixed<2>(d, candidates);
+        default: return digit_peers_fixed<1>(d, candidates);
+    }
+}
+
 template <bool FIRST, int THREADS, int ITEMS>
 __global__ __launch_bounds__(THREADS) void downsweep_kernel(
     const int32_t* __restrict__ keys_in, const int32_t* __restrict__ vals_in, int64_t n_slots,
@@ -271,6 +298,8 @@ __global__ __launch_bounds__(THREADS) void downsweep_kernel(
     // Stable rank inside the wave's 1024 consecutive keys: for every group of 64
     // keys, the lanes holding the same digit are found with one ballot per digit
     // bit; the lowest such lane advances the wave's running count of the digit.
+    // Every live lane reads the count before that lane writes it: the LDS executes
+    // a wavefront's operations in order.
 #pragma unroll
     for (int r = 0; r < ITEMS; ++r) {
         if ((uint32_t)(r * 64) >= wave_live) {  // the same for the whole wave: nothing left to rank
@@ -279,25 +308,18 @@ __global__ __launch_bounds__(THREADS) void downsweep_kernel(
         }
         const bool live = key[r] >= 0;
         const uint32_t d = ((uint32_t)key[r] >> shift) & mask;
-        uint64_t peers = __ballot(live);
-        for (int b = 0; b < bits; ++b) {
-            const bool bit = (d >> b) & 1u;
-            const uint64_t bal = __ballot(live && bit);
-            peers &= bit ? bal : ~bal;
-        }
+        const uint64_t peers = digit_peers(d, __ballot(live), bits);
+        const uint32_t below = __builtin_amdgcn_mbcnt_hi((uint32_t)(peers >> 32),
+                                                         __builtin_amdgcn_mbcnt_lo((uint32_t)peers, 0u));
         uint32_t old = 0;
-        int leader = lane;
         if (live) {
-            leader = __ffsll((unsigned long long)peers) - 1;
-            if (lane == leader) {
-                old = wave_hist[wave][d];
-                wave_hist[wave][d] = old + (uint32_t)__popcll(peers);
-            }
+            old = wave_hist[wave][d];
+            if (below == 0u) wave_hist[wave][d] = old + (uint32_t)__popcll(peers);
         }
-        // the next group of 64 keys may read this counter from another lane of the wave
+        // the next group of 64 keys reads these counters
         __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-        old = __shfl(old, leader, 64);
-        rank[r] = old + (uint32_t)__popcll(peers & lanes_below(lane));
+        __builtin_amdgcn_wave_barrier();
+        rank[r] = old + below;
     }
     __syncthreads();
 
