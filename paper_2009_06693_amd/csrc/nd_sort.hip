@@ -165,33 +165,6 @@ __global__ __launch_bounds__(kBinscanThreads) void binscan_kernel(uint32_t* __re
     if (threadIdx.x == 0) bin_total[blockIdx.x] = carry;
 }
 
-// The lanes of the wavefront that hold digit d (among the lanes of `candidates`): one ballot per
-// digit bit, the bit spread over the lane's word so that "my bit equals theirs" is one XNOR per half.
-template <int BITS>
-__device__ __forceinline__ uint64_t digit_peers_fixed(uint32_t d, uint64_t candidates) {
-    uint32_t lo = (uint32_t)candidates, hi = (uint32_t)(candidates >> 32);
-#pragma unroll
-    for (int b = 0; b < BITS; ++b) {
-        const uint32_t mine = (uint32_t)__builtin_amdgcn_sbfe((int)d, (uint32_t)b, 1u);  // all ones or zero
-        const uint64_t theirs = __ballot(mine != 0u);
-        lo &= ~((uint32_t)theirs ^ mine);
-        hi &= ~((uint32_t)(theirs >> 32) ^ mine);
-    }
-    return ((uint64_t)hi << 32) | lo;
-}
-__device__ __forceinline__ uint64_t digit_peers(uint32_t d, uint64_t candidates, int bits) {
-    switch (bits) {  // the same for the whole launch
-        case 8: return digit_peers_fixed<8>(d, candidates);
-        case 7: return digit_peers_fixed<7>(d, candidates);
-        case 6: return digit_peers_fixed<6>(d, candidates);
-        case 5: return digit_peers_fixed<5>(d, candidates);
-        case 4: return digit_peers_fixed<4>(d, candidates);
-        case 3: return digit_peers_fixed<3>(d, candidates);
-        case 2: return digit_peers_fixed<2>(d, candidates);
-        default: return digit_peers_fixed<1>(d, candidates);
-    }
-}
-
 template <bool FIRST, int THREADS, int ITEMS>
 __global__ __launch_bounds__(THREADS) void downsweep_kernel(
     const int32_t* __restrict__ keys_in, const int32_t* __restrict__ vals_in, int64_t n_slots,

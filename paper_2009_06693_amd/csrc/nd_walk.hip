@@ -271,25 +271,18 @@ __global__ __launch_bounds__(THREADS) void walk_window_kernel(GraphView<OffT> g,
                         val[r] = s_val[in][idx];
                     }
                     const uint32_t dg = ((uint32_t)key[r] >> shift) & mask;
-                    uint64_t peers = __ballot(live);
-                    for (int b = 0; b < bits; ++b) {
-                        const bool bit = (dg >> b) & 1u;
-                        const uint64_t bal = __ballot(live && bit);
-                        peers &= bit ? bal : ~bal;
-                    }
+                    const uint64_t peers = digit_peers(dg, __ballot(live), bits);
+                    const uint32_t below = __builtin_amdgcn_mbcnt_hi((uint32_t)(peers >> 32),
+                                                                     __builtin_amdgcn_mbcnt_lo((uint32_t)peers, 0u));
                     uint32_t old = 0;
-                    int leader = lane;
-                    if (live) {
-                        leader = __ffsll((unsigned long long)peers) - 1;
-                        if (lane == leader) {
-                            old = s_hist[wv][dg];
-                            s_hist[wv][dg] = old + (uint32_t)__popcll(peers);
-                        }
+                    if (live) {  // every live lane reads the count before the lowest of its peers writes it
+                        old = s_hist[wv][dg];
+                        if (below == 0u) s_hist[wv][dg] = old + (uint32_t)__popcll(peers);
                     }
-                    // the next 64 pairs may read this counter from another lane of the wave
+                    // the next 64 pairs read these counters
                     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-                    old = __shfl(old, leader, 64);
-                    rank[r] = old + (uint32_t)__popcll(peers & lanes_below(lane));
+                    __builtin_amdgcn_wave_barrier();
+                    rank[r] = old + below;
                 }
                 __syncthreads();
                 {
