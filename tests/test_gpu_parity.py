@@ -362,7 +362,8 @@ def test_device_resident_graph_source(small_w):
 
 # ----------------------------------------------------------------------------- grouping on its own
 @pytest.mark.parametrize("n,V", [(0, 10), (1, 1), (100, 3), (8192, 300), (8193, 70000),
-                                 (200001, 1 << 22), (50000, 2)])
+                                 (200001, 1 << 22), (50000, 2),
+                                 (5000, 7), (5000, 100), (70000, 200)])   # digits of 3, 7 and 8 bits in one pass
 def test_group_by_transit_matches_stable_sort(n, V):
     rng = np.random.default_rng(n + V)
     t = rng.integers(0, V, size=n, dtype=np.int32)
