@@ -95,11 +95,24 @@ __global__ __launch_bounds__(THREADS) void upsweep_kernel(
         }
     }
     if (FIRST && base < n) {
-        for (int i = tid; i < kTile; i += THREADS) {
-            const int64_t idx = base + i;  // a wavefront covers 64 consecutive slots
-            int32_t k = ND_NULL_VERTEX;
+        // all of the thread's keys are requested before the first is looked at
+        int32_t mine[ITEMS];
+        if (base + kTile <= n) {  // a whole tile (all but the last): nothing to test
+            const int32_t* kp = keys + base + tid;
+#pragma unroll
+            for (int r = 0; r < ITEMS; ++r) mine[r] = kp[r * THREADS];
+        } else {
+#pragma unroll
+            for (int r = 0; r < ITEMS; ++r) {
+                const int64_t idx = base + r * THREADS + tid;
+                mine[r] = idx < n ? keys[idx] : ND_NULL_VERTEX;
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < ITEMS; ++r) {
+            const int64_t idx = base + r * THREADS + tid;  // a wavefront covers 64 consecutive slots
+            int32_t k = mine[r];
             if (idx < n) {
-                k = keys[idx];
                 if (FIRST && (k >= V || k < ND_NULL_VERTEX)) {
                     bad = true;
                     k = ND_NULL_VERTEX;
@@ -219,21 +232,34 @@ __global__ __launch_bounds__(THREADS) void downsweep_kernel(
 
     int32_t key[ITEMS], val[ITEMS];
     uint32_t rank[ITEMS];
+    if (base + kTile <= n) {  // a whole tile (all but the last): nothing to test, one base address
+        const int64_t first = base + (int64_t)wave * kPerWave + lane;
+        const int32_t* kp = keys_in + first;
+        const int32_t* vp = FIRST ? nullptr : vals_in + first;
 #pragma unroll
-    for (int r = 0; r < ITEMS; ++r) {
-        const int64_t idx = base + (int64_t)wave * kPerWave + r * 64 + lane;
-        int32_t k = ND_NULL_VERTEX, v = 0;
-        if (idx < n) {
-            k = keys_in[idx];
-            if (FIRST) {
-                if (k >= V || k < 0) k = ND_NULL_VERTEX;
-                v = (int32_t)idx;
-            } else {
-                v = vals_in[idx];
-            }
+        for (int r = 0; r < ITEMS; ++r) {
+            int32_t k = kp[r * 64];
+            if (FIRST && (k >= V || k < 0)) k = ND_NULL_VERTEX;
+            key[r] = k;
+            val[r] = FIRST ? (int32_t)(first + r * 64) : vp[r * 64];
         }
-        key[r] = k;
-        val[r] = v;
+    } else {
+#pragma unroll
+        for (int r = 0; r < ITEMS; ++r) {
+            const int64_t idx = base + (int64_t)wave * kPerWave + r * 64 + lane;
+            int32_t k = ND_NULL_VERTEX, v = 0;
+            if (idx < n) {
+                k = keys_in[idx];
+                if (FIRST) {
+                    if (k >= V || k < 0) k = ND_NULL_VERTEX;
+                    v = (int32_t)idx;
+                } else {
+                    v = vals_in[idx];
+                }
+            }
+            key[r] = k;
+            val[r] = v;
+        }
     }
     // Pass 0 sees the slots without a transit as well (nearly half of them in the k-hop
     // workload on a graph with many isolated vertices).  The wave squeezes them out of its
@@ -313,7 +339,7 @@ __global__ __launch_bounds__(THREADS) void downsweep_kernel(
         if (tid == 0) scan_tmp[kWaves + 1] = total;  // live keys of the tile
     }
     __syncthreads();
-    const uint32_t tile_live = scan_tmp[kWaves + 1];
+    const uint32_t tile_live = wave_uniform(scan_tmp[kWaves + 1]);
 
 #pragma unroll
     for (int r = 0; r < ITEMS; ++r) {
