@@ -47,7 +47,24 @@ __global__ __launch_bounds__(kSegThreads) void seg_count_kernel(const int32_t* _
     const int64_t P = ctl->P;
     const int64_t base = (int64_t)blockIdx.x * kSegTile + (int64_t)wave * kSegPerWave;
     uint32_t cnt = 0;
-    if (base < P) {
+    if (base + kSegPerWave <= P) {
+        // a whole chunk (all but the last): every load is issued before the first comparison, and
+        // the key before a round's first is the last key of the round before, passed in a register
+        constexpr int kRounds = kSegPerWave / 256;
+        const int4* kp = reinterpret_cast<const int4*>(keys + base) + lane;  // base is a multiple of 4
+        int4 v[kRounds];
+#pragma unroll
+        for (int r = 0; r < kRounds; ++r) v[r] = kp[r * 64];
+        int32_t before = base > 0 ? keys[base - 1] : -3;  // the same in all lanes
+#pragma unroll
+        for (int r = 0; r < kRounds; ++r) {
+            int32_t prev = __shfl_up(v[r].w, 1, 64);
+            if (lane == 0) prev = before;
+            cnt += (v[r].x != prev ? 1u : 0u) + (v[r].y != v[r].x ? 1u : 0u) + (v[r].z != v[r].y ? 1u : 0u) +
+                   (v[r].w != v[r].z ? 1u : 0u);
+            before = __builtin_amdgcn_readlane(v[r].w, 63);
+        }
+    } else if (base < P) {
 #pragma unroll
         for (int r = 0; r < kSegPerWave / 256; ++r) {
             const int64_t idx = base + r * 256 + lane * 4;
@@ -114,6 +131,32 @@ __global__ __launch_bounds__(kSegThreads) void seg_write_kernel(const int32_t* _
     if (base >= P) return;
     uint32_t gid = tile_offs[(int64_t)blockIdx.x * kSegWaves + wave];  // groups that start before this wave
     // group ids by ballot prefix
+    if (base + kSegPerWave <= P) {
+        // a whole chunk (all but the last): all keys are requested first; the key before a round's
+        // first is the last key of the round before, passed in a register
+        constexpr int kRounds = kSegPerWave / 64;
+        const int32_t* kp = keys + base + lane;
+        int32_t k[kRounds];
+#pragma unroll
+        for (int r = 0; r < kRounds; ++r) k[r] = kp[r * 64];
+        int32_t before = base > 0 ? keys[base - 1] : -3;  // the same in all lanes
+#pragma unroll
+        for (int r = 0; r < kRounds; ++r) {
+            int32_t prev = __shfl_up(k[r], 1, 64);
+            if (lane == 0) prev = before;
+            const bool h = k[r] != prev;
+            const uint64_t bal = __ballot(h);
+            if (h) {
+                const uint32_t g = gid + __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32),
+                                                                   __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
+                g_key[g] = k[r];
+                g_start[g] = (int32_t)(base + r * 64 + lane);
+            }
+            gid += (uint32_t)__popcll(bal);
+            before = __builtin_amdgcn_readlane(k[r], 63);
+        }
+        return;
+    }
     for (int r = 0; r < kSegPerWave / 64; ++r) {
         int32_t k;
         const int64_t idx = base + r * 64 + lane;
