@@ -58,6 +58,15 @@ inline GraphView<OffT> view_of(const Graph& g) {
     return GraphView<OffT>{(const OffT*)g.off, g.col, g.wq, g.cumq, g.maxwq, (int32_t)g.V};
 }
 
+// Length of row v, given where it starts.  A row is shorter than 2^32, so the low words of the two
+// offsets suffice, and with 64-bit offsets the high word of the second one is not fetched: a
+// register that a load in flight is about to fill and nobody reads is reused at once, and that use
+// waits for the load (in the k-hop loop this cost a tenth of the kernel's time).
+template <typename OffT>
+__device__ __forceinline__ uint32_t row_length(const GraphView<OffT>& g, int32_t v, uint64_t row_start) {
+    return reinterpret_cast<const uint32_t*>(g.off + v + 1)[0] - (uint32_t)row_start;
+}
+
 int graph_create(Graph** out, int64_t V, int64_t E, const void* off, int off64, const int32_t* col,
                  const float* w, int src_is_device, hipStream_t stream);
 void graph_destroy(Graph* g);

@@ -78,7 +78,7 @@ __device__ __forceinline__ int32_t draw_node2vec(const GraphView<OffT>& g, const
     if (a.has_prev) {
         t = t_prev;
         rs_t = (uint64_t)g.off[t];
-        deg_t = (uint32_t)((uint64_t)g.off[t + 1] - rs_t);
+        deg_t = row_length(g, t, rs_t);
     }
     const uint32_t b_lo = a.b_com < a.b_far ? a.b_com : a.b_far;
     const uint32_t b_hi = a.b_com < a.b_far ? a.b_far : a.b_com;

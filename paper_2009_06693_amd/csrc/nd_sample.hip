@@ -66,7 +66,7 @@ __global__ __launch_bounds__(256) void sample_sp_kernel(GraphView<OffT> g, DrawA
     int32_t res = ND_NULL_VERTEX;
     if (v >= 0) {
         const uint64_t rs = (uint64_t)g.off[v];
-        const uint32_t deg = (uint32_t)((uint64_t)g.off[v + 1] - rs);
+        const uint32_t deg = row_length(g, v, rs);
         if (deg > 0)
             res = draw_for_slot<DRAW>(g, a, v, deg, q, jj, g.col + rs,
                                       DRAW == kDrawWeighted ? g.cumq + rs : nullptr,
@@ -121,7 +121,7 @@ __device__ __forceinline__ PairCtx load_pair_row(const GraphView<OffT>& g, const
     uint32_t heavy = 0;
     if (HEAVY) heavy = (heavy_bits[(uint32_t)c.v >> 5] >> ((uint32_t)c.v & 31u)) & 1u;
     c.rs = (uint64_t)g.off[c.v];
-    c.deg = (uint32_t)((uint64_t)g.off[c.v + 1] - c.rs);
+    c.deg = row_length(g, c.v, c.rs);
     c.mine = k.in_range && heavy == 0u;
     return c;
 }
@@ -242,7 +242,7 @@ __device__ __forceinline__ void workgroup_draws(const GraphView<OffT>& g, const 
     const int32_t v = g_key[gid];
     const uint32_t start = (uint32_t)g_start[gid];
     const uint64_t rs = (uint64_t)g.off[v];
-    const uint32_t deg = (uint32_t)((uint64_t)g.off[v + 1] - rs);
+    const uint32_t deg = row_length(g, v, rs);
     const uint32_t ndraws = d1 - d0;
     bool stage = deg > 0 && deg <= cap;
     if (a.lds_policy == 1) stage = false;
@@ -528,7 +528,7 @@ __global__ __launch_bounds__(256) void unique_kernel(GraphView<OffT> g, UniqueAr
                 const uint32_t pj = fastdiv(j, a.div_m);
                 const int32_t v = a.parents[(uint64_t)s * a.W_prev + pj];  // live: it drew in round 0
                 const uint64_t rs = (uint64_t)g.off[v];
-                const uint32_t deg = (uint32_t)((uint64_t)g.off[v + 1] - rs);
+                const uint32_t deg = row_length(g, v, rs);
                 if (p_held[pj] >= deg) {
                     // the parent's slots already hold as many distinct vertices as its row has entries:
                     // whatever this slot draws is held, now and in every later round

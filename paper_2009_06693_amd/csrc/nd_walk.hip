@@ -222,7 +222,7 @@ __global__ __launch_bounds__(THREADS) void walk_window_kernel(GraphView<OffT> g,
             next[it] = ND_NULL_VERTEX;
             const int32_t v = alive && !grouped[it] ? cur[it] : 0;  // all row offsets first: independent loads
             rs[it] = (uint64_t)g.off[v];
-            deg[it] = (uint32_t)((uint64_t)g.off[v + 1] - rs[it]);
+            deg[it] = row_length(g, v, rs[it]);
         }
 #pragma unroll
         for (int it = 0; it < ITEMS; ++it) {
@@ -349,7 +349,7 @@ __global__ __launch_bounds__(THREADS) void walk_window_kernel(GraphView<OffT> g,
                 }
                 const uint32_t p1 = lo;
                 const uint64_t hrs = (uint64_t)g.off[v];
-                const uint32_t hdeg = (uint32_t)((uint64_t)g.off[v + 1] - hrs);
+                const uint32_t hdeg = row_length(g, v, hrs);
                 bool do_stage = hdeg > 0 && hdeg <= (uint32_t)N && d.lds_policy != 1;
                 if (d.lds_policy == 0) do_stage = do_stage && hdeg >= 128u && hdeg / 4u <= p1 - p0;
                 const int32_t* adj = g.col + hrs;
@@ -380,7 +380,7 @@ __global__ __launch_bounds__(THREADS) void walk_window_kernel(GraphView<OffT> g,
                     if (l & kDoneMark) continue;
                     const int32_t v = skey[p];
                     const uint64_t prs = (uint64_t)g.off[v];
-                    const uint32_t pdeg = (uint32_t)((uint64_t)g.off[v + 1] - prs);
+                    const uint32_t pdeg = row_length(g, v, prs);
                     s_res[l] = draw_one<DRAW, OffT>(g, d, v, prs, pdeg, d.sample_base + base_slot + l,
                                                     s_prev[DRAW == kDrawNode2vec ? l : 0], g.col + prs);
                 }
