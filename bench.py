@@ -30,8 +30,8 @@ HBM_PEAK_GBS = 8000.0
 # gives: x2.0 and x1.0), averaged over the launches of one call.  Sources: the counter tables in
 # profiles/c5_khop_tp_rocprofv3.md and profiles/c5_deepwalk_tp_rocprofv3.md.  None where not profiled.
 MEASURED_TRAFFIC_BYTES = {
-    ("c5_khop", "tp", "sample_sub"): 3032694586,        # 1,236.4 MiB fetched + 1,655.8 MiB written per launch
-    ("c5_deepwalk", "tp", "walk_window"): 52894748779,  # 48,819.4 MiB fetched + 1,625.0 MiB written per launch
+    ("c5_khop", "tp", "sample_sub"): 3162426811,        # 1,337.6 MiB fetched + 1,678.4 MiB written per launch
+    ("c5_deepwalk", "tp", "walk_window"): 52888034690,  # 48,813.0 MiB fetched + 1,625.0 MiB written per launch
 }
 
 WORKLOADS = {
