@@ -42,10 +42,13 @@ constexpr int kEdgeThreads = 1024;  // two workgroups (76 KB of LDS each) fill a
 constexpr int kEdgeUnroll = 4;      // adjacency loads in flight per lane and step
 constexpr uint32_t kBatch = 64 * kEdgeUnroll;  // adjacency entries a wavefront takes per step
 constexpr int kBitWords = 2048;     // the vertex map: 65,536 bits, indexed by the vertex id folded to 16 bits
-constexpr uint32_t kQueueCap = 64 + kBatch;    // fewer than 64 left over plus one step's entries
+constexpr uint32_t kQueueCap = 64 + 64;        // fewer than 64 left over plus a quarter step's entries
+constexpr uint32_t kOutCap = 64 + 64;          // filling pass: edges of the current transit not yet written
 constexpr int kMaxSlots = 2048;  // new vertices per sample (ND_MAX_EDGE_SLOTS)
-constexpr size_t kEdgeLdsBytes = (size_t)kMaxSlots * 8 + (size_t)4 * kMaxSlots * 4 + (size_t)kBitWords * 4 +
-                                 (size_t)(kEdgeThreads / 64) * kQueueCap * 4;
+constexpr int kChunk = 2048;     // transit slots of a sample that are sorted and de-duplicated together
+constexpr size_t kEdgeLdsBytes = (size_t)kMaxSlots * 8 + (size_t)2 * kMaxSlots * 4 + (size_t)kBitWords * 4 +
+                                 (size_t)(kEdgeThreads / 64) * (kQueueCap + kOutCap) * 4 + (size_t)kChunk * 8 +
+                                 (size_t)kChunk * 2;
 constexpr int kScanThreads = 256;
 constexpr int kScanItems = 16;
 constexpr int kScanTile = kScanThreads * kScanItems;
@@ -55,7 +58,7 @@ struct EdgeArgs {
     const int32_t* sampled;   // [S][m]
     uint32_t n_prev, m;
     uint32_t m2;              // power of two >= m
-    uint32_t hash_shift;      // 32 - log2(4 * m2)
+    uint32_t hash_shift;      // 32 - log2(2 * m2)
     int32_t* counts;          // count pass: [S * n_prev]
     const int64_t* row_ptr;   // fill pass
     int32_t* edge_slot;
@@ -80,16 +83,77 @@ __device__ __forceinline__ void wave_lds_order() {
     __builtin_amdgcn_wave_barrier();
 }
 
+// Bitonic sorting network over the n2 (at most 2 * kEdgeThreads) keys of an LDS array, ascending;
+// every thread of the workgroup calls it, after a barrier that made the keys visible, and it ends
+// with one.  The keys live in registers, two per thread (keys t and t + kEdgeThreads; missing ones
+// count as the largest value): of the 66 compare-exchange steps of 2,048 keys, the 51 whose partner
+// is less than 64 keys away are lane exchanges inside the wavefront, one pairs a thread's own two
+// keys, and only 14 go through LDS and a workgroup barrier.  (With every step through LDS the sort
+// took 54 us per workgroup, more than streaming the adjacency lists of 64 transits.)
+__device__ __forceinline__ uint64_t exchange_step(uint64_t mine, uint64_t theirs, bool keep_min) {
+    const bool theirs_smaller = theirs < mine;
+    return (theirs_smaller == keep_min) ? theirs : mine;
+}
+__device__ __forceinline__ uint64_t lane_xor64(uint64_t x, int j) {
+    const uint32_t lo = (uint32_t)__shfl_xor((int)(uint32_t)x, j, 64);
+    const uint32_t hi = (uint32_t)__shfl_xor((int)(uint32_t)(x >> 32), j, 64);
+    return ((uint64_t)hi << 32) | lo;
+}
+__device__ __forceinline__ void bitonic_sort_lds(uint64_t* keys, uint32_t n2, uint32_t tid) {
+    constexpr uint32_t T = (uint32_t)kEdgeThreads;
+    const bool two = n2 > T;  // the same for the whole workgroup
+    const uint32_t N = two ? 2u * T : T;
+    uint64_t k0 = tid < n2 ? keys[tid] : ~0ull;
+    uint64_t k1 = (two && tid + T < n2) ? keys[tid + T] : ~0ull;
+    __syncthreads();  // everybody has its keys: the array is free for the exchanges below
+    for (uint32_t k = 2; k <= N; k <<= 1) {
+        const bool asc0 = (tid & k) == 0, asc1 = ((tid + T) & k) == 0;
+        for (uint32_t j = k >> 1; j > 0; j >>= 1) {
+            if (j == T) {  // a thread's own two keys; tid < T <= k / 2, so this pair sorts ascending
+                if (k1 < k0) {
+                    const uint64_t t = k0;
+                    k0 = k1;
+                    k1 = t;
+                }
+                continue;
+            }
+            uint64_t p0, p1 = ~0ull;
+            if (j >= 64u) {
+                keys[tid] = k0;
+                if (two) keys[tid + T] = k1;
+                __syncthreads();
+                p0 = keys[tid ^ j];
+                if (two) p1 = keys[(tid ^ j) + T];
+                __syncthreads();
+            } else {
+                p0 = lane_xor64(k0, (int)j);
+                if (two) p1 = lane_xor64(k1, (int)j);
+            }
+            const bool lower = (tid & j) == 0;  // my key is the pair's first (also for key t + T: j < T)
+            k0 = exchange_step(k0, p0, lower == asc0);
+            if (two) k1 = exchange_step(k1, p1, lower == asc1);
+        }
+    }
+    keys[tid] = k0;  // the array holds at least N entries
+    if (two) keys[tid + T] = k1;
+    __syncthreads();
+}
+
 template <typename OffT, bool FILL>
 __global__ __launch_bounds__(kEdgeThreads) void edges_kernel(GraphView<OffT> g, EdgeArgs a) {
     extern __shared__ __align__(16) unsigned char s_dyn[];
     uint64_t* s_sorted = (uint64_t*)s_dyn;                // [kMaxSlots] (vertex << 32 | slot), ascending; ~0 = none
-    uint32_t* table = (uint32_t*)(s_sorted + kMaxSlots);  // [4 * kMaxSlots] entries as described above
-    uint32_t* s_bits = table + 4 * kMaxSlots;             // [kBitWords] bit set: some sample vertex hashes here
+    uint32_t* table = (uint32_t*)(s_sorted + kMaxSlots);  // [2 * kMaxSlots] entries as described above
+    uint32_t* s_bits = table + 2 * kMaxSlots;             // [kBitWords] bit set: some sample vertex hashes here
     int32_t* s_queue = (int32_t*)(s_bits + kBitWords);    // per wavefront: entries that passed the bit test
+    int32_t* s_out = s_queue + (kEdgeThreads / 64) * kQueueCap;  // per wavefront: edges waiting to be written
+    uint64_t* s_trans = (uint64_t*)(s_out + (kEdgeThreads / 64) * kOutCap);  // [kChunk] (transit << 32 | slot), sorted
+    uint16_t* s_heads = (uint16_t*)(s_trans + kChunk);    // [kChunk] where each distinct transit starts in s_trans
+    __shared__ uint32_t s_scan[kEdgeThreads / 64 + 1];
+    __shared__ uint32_t s_items[2];                       // distinct transits and live slots of the chunk
     const uint32_t b = blockIdx.x;
     const uint32_t tid = threadIdx.x;
-    const uint32_t mask = 4u * a.m2 - 1u;
+    const uint32_t mask = 2u * a.m2 - 1u;
     const int32_t* sampled = a.sampled + (uint64_t)b * a.m;
     bool bad = false;
 
@@ -105,30 +169,14 @@ __global__ __launch_bounds__(kEdgeThreads) void edges_kernel(GraphView<OffT> g, 
         }
         s_sorted[i] = key;
     }
-    for (uint32_t i = tid; i < 4u * a.m2; i += kEdgeThreads) table[i] = kEmpty;
+    for (uint32_t i = tid; i < 2u * a.m2; i += kEdgeThreads) table[i] = kEmpty;
     for (uint32_t i = tid; i < (uint32_t)kBitWords; i += kEdgeThreads) s_bits[i] = 0u;
     __syncthreads();
 
-    // bitonic sorting network over m2 keys
-    for (uint32_t k = 2; k <= a.m2; k <<= 1) {
-        for (uint32_t j = k >> 1; j > 0; j >>= 1) {
-            for (uint32_t i = tid; i < a.m2; i += kEdgeThreads) {
-                const uint32_t p = i ^ j;
-                if (p > i) {
-                    const uint64_t x = s_sorted[i], y = s_sorted[p];
-                    const bool ascending = (i & k) == 0;
-                    if ((x > y) == ascending) {
-                        s_sorted[i] = y;
-                        s_sorted[p] = x;
-                    }
-                }
-            }
-            __syncthreads();
-        }
-    }
+    bitonic_sort_lds(s_sorted, a.m2, tid);
 
     // the first entry of every run of equal vertices puts the run into the table (the table has
-    // four times as many places as there can be runs, so the probe loops end)
+    // twice as many places as there can be runs, so the probe loops end)
     for (uint32_t k = tid; k < a.m2; k += kEdgeThreads) {
         const uint64_t key = s_sorted[k];
         if (key == ~0ull) continue;
@@ -149,235 +197,303 @@ __global__ __launch_bounds__(kEdgeThreads) void edges_kernel(GraphView<OffT> g, 
     }
     __syncthreads();
 
-    // ---- the wavefronts stream the adjacency lists of the sample's transits, a row at a time each.
-    // Everything about a row is the same in all lanes of its wavefront and is kept in scalar
-    // registers.  The loop runs over steps of up to kBatch entries of a row; the entries of the next
-    // step (the same row's or the next row's) are requested before the current step is worked on,
-    // and so are, one and two rows ahead, the offsets and the transit of the rows to come.
+    // ---- The sample's transits, kChunk slots at a time, are sorted by vertex in LDS: layer samples
+    // hold well-connected vertices many times over (569 distinct among the 2,048 transits of the
+    // benchmark's second step), and a vertex's adjacency list is streamed once for all the slots
+    // that hold it.  The wavefronts then take one distinct transit each at a time.
+    // Everything about such an item is the same in all lanes of its wavefront and is kept in scalar
+    // registers.  The loop runs over steps of up to kBatch entries of a list; the entries of the next
+    // step (the same item's or the next item's) and the offsets of the item after are requested
+    // before the current step is worked on.
     constexpr uint32_t kStride = kEdgeThreads / 64;
     const int lane = lane_id();
     const uint32_t wave = wave_uniform((uint32_t)wave_id());
     int32_t* queue = s_queue + wave * kQueueCap;
+    int32_t* obuf = s_out + wave * kOutCap;
     const uint64_t row0 = (uint64_t)b * a.n_prev;
 
-    auto transit_of = [&](uint32_t row) -> int32_t {  // as stored; NULL beyond the last row
-        return row < a.n_prev ? a.transits[row0 + row] : ND_NULL_VERTEX;
-    };
-    auto checked = [&](int32_t v) -> int32_t {
-        v = wave_uniform(v);
-        if (v >= g.V || v < ND_NULL_VERTEX) {
-            bad = true;
-            v = ND_NULL_VERTEX;
+    for (uint32_t chunk0 = 0; chunk0 < a.n_prev; chunk0 += (uint32_t)kChunk) {
+        const uint32_t n_chunk = a.n_prev - chunk0 < (uint32_t)kChunk ? a.n_prev - chunk0 : (uint32_t)kChunk;
+        uint32_t n2 = 64;
+        while (n2 < n_chunk) n2 <<= 1;
+        for (uint32_t i = tid; i < n2; i += kEdgeThreads) {
+            uint64_t key = ~0ull;
+            if (i < n_chunk) {
+                int32_t v = a.transits[row0 + chunk0 + i];
+                if (v >= g.V || v < ND_NULL_VERTEX) {
+                    bad = true;
+                    v = ND_NULL_VERTEX;
+                }
+                if (v >= 0) key = ((uint64_t)(uint32_t)v << 32) | (chunk0 + i);
+                else if (!FILL) a.counts[row0 + chunk0 + i] = 0;  // a slot without a transit has no edges
+            }
+            s_trans[i] = key;
         }
-        return v;
-    };
-    // the row whose entries are being requested
-    uint32_t t = wave;
-    uint64_t rs = 0, deg = 0;   // where its adjacency list starts and how long it is (0: nothing to stream)
-    uint64_t e0 = 0;            // the next entry of it to request
-    int64_t wb = 0;             // FILL: where its output starts
-    // one row ahead: transit known, offsets (FILL: row pointers) requested; two ahead: transit requested
-    int32_t tv_a = ND_NULL_VERTEX, tv_b = ND_NULL_VERTEX;
-    OffT off_a0 = 0, off_a1 = 0;
-    int64_t rp_a0 = 0, rp_a1 = 0;
-    auto request_a = [&]() {
-        off_a0 = off_a1 = 0;
-        if (tv_a >= 0) {
-            off_a0 = g.off[tv_a];
-            off_a1 = g.off[tv_a + 1];
+        __syncthreads();
+        bitonic_sort_lds(s_trans, n2, tid);
+        {   // where the distinct transits start (two positions per thread: n2 <= 2 * kEdgeThreads)
+            bool head[2];
+            uint32_t mine = 0, live = 0;
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const uint32_t i = tid * 2u + (uint32_t)e;
+                head[e] = false;
+                if (i < n2 && s_trans[i] != ~0ull) {
+                    ++live;
+                    head[e] = i == 0 || (uint32_t)(s_trans[i - 1] >> 32) != (uint32_t)(s_trans[i] >> 32);
+                }
+                mine += head[e] ? 1u : 0u;
+            }
+            // one scan for both counts (each at most 2,048): heads in the low half, live slots in the high
+            uint32_t total;
+            uint32_t at = block_exclusive_scan<uint32_t, kEdgeThreads>(mine | (live << 16), s_scan, &total) & 0xFFFFu;
+            if (tid == 0) {
+                s_items[0] = total & 0xFFFFu;
+                s_items[1] = total >> 16;
+            }
+#pragma unroll
+            for (int e = 0; e < 2; ++e)
+                if (head[e]) s_heads[at++] = (uint16_t)(tid * 2u + (uint32_t)e);
         }
-        if constexpr (FILL) {
+        __syncthreads();
+        const uint32_t n_items = wave_uniform(s_items[0]);
+        const uint32_t n_live = wave_uniform(s_items[1]);  // the live slots are the first n_live of s_trans
+
+        // the item whose entries are being requested: positions [p0, p1) of s_trans hold its slots
+        uint32_t item = wave;
+        uint32_t p0 = 0, p1 = 0;
+        uint64_t rs = 0, deg = 0;   // where its adjacency list starts and how long it is (0: nothing to stream)
+        uint64_t e0 = 0;            // the next entry of it to request
+        // one item ahead: offsets (FILL: row pointers of its first slot) requested
+        OffT off_a0 = 0, off_a1 = 0;
+        int64_t rp_a0 = 0, rp_a1 = 0;
+        auto slots_of = [&](uint32_t it, uint32_t* first, uint32_t* last) {
+            *first = s_heads[it];
+            *last = it + 1u < n_items ? (uint32_t)s_heads[it + 1u] : n_live;
+        };
+        auto request_a = [&](uint32_t it) {  // offsets and row pointers of item `it`
+            off_a0 = off_a1 = 0;
             rp_a0 = rp_a1 = 0;
-            if (t + kStride < a.n_prev) {
-                rp_a0 = a.row_ptr[row0 + t + kStride];
-                rp_a1 = a.row_ptr[row0 + t + kStride + 1];
-            }
-        }
-    };
-    auto advance = [&]() {
-        t += kStride;
-        rs = wave_uniform((uint64_t)off_a0);
-        deg = wave_uniform((uint64_t)off_a1) - rs;
-        if constexpr (FILL) {
-            wb = wave_uniform(rp_a0);
-            if (wave_uniform(rp_a1) == wb) deg = 0;  // the counting pass found nothing in this row
-        }
-        e0 = 0;
-        tv_a = checked(tv_b);
-        request_a();
-        tv_b = transit_of(t + 2 * kStride);
-    };
-    auto skip_empty_rows = [&]() {
-        while (t < a.n_prev && deg == 0) {
-            if constexpr (!FILL)
-                if (lane == 0) a.counts[row0 + t] = 0;
-            advance();
-        }
-    };
-    auto request_entries = [&](int32_t (&u)[kEdgeUnroll]) {
-        const int32_t* p = g.col + rs + e0;
-        const uint64_t left = deg - e0;
-        const uint32_t cnt = left < kBatch ? (uint32_t)left : kBatch;
-        if (cnt == kBatch) {  // a full step, the common case: nothing to test
-#pragma unroll
-            for (int r = 0; r < kEdgeUnroll; ++r) u[r] = p[r * 64 + lane];
-            return;
-        }
-#pragma unroll
-        for (int r = 0; r < kEdgeUnroll; ++r) {
-            u[r] = ND_NULL_VERTEX;
-            // the test is the same in all lanes; inside the last 64 entries a lane past the end
-            // reads the last entry again instead of branching (and drops it when it looks at it:
-            // looking at it here would wait for each load in turn)
-            if ((uint32_t)r * 64u < cnt) {
-                const uint32_t e = (uint32_t)r * 64u + (uint32_t)lane;
-                u[r] = p[e < cnt ? e : cnt - 1u];
-            }
-        }
-    };
-
-    {   // the pipeline's first row is loaded directly
-        const int32_t tv = checked(transit_of(t));
-        if (tv >= 0) {
-            rs = wave_uniform((uint64_t)g.off[tv]);
-            deg = wave_uniform((uint64_t)g.off[tv + 1]) - rs;
-        }
-        if constexpr (FILL) {
-            if (t < a.n_prev) {
-                wb = wave_uniform(a.row_ptr[row0 + t]);
-                if (wave_uniform(a.row_ptr[row0 + t + 1]) == wb) deg = 0;
-            }
-        }
-        tv_a = checked(transit_of(t + kStride));
-        request_a();
-        tv_b = transit_of(t + 2 * kStride);
-    }
-    skip_empty_rows();
-    int32_t u_next[kEdgeUnroll];
-#pragma unroll
-    for (int r = 0; r < kEdgeUnroll; ++r) u_next[r] = 0;
-    if (t < a.n_prev) request_entries(u_next);
-
-    uint32_t queued = 0;  // entries in the queue (the same in all lanes)
-    uint32_t count = 0;   // counting pass: my share of the row's edges
-    int64_t wbase = wb;   // filling pass: where the row's next edge goes
-    while (t < a.n_prev) {
-        // ---- the step whose entries have been requested
-        int32_t u[kEdgeUnroll];
-#pragma unroll
-        for (int r = 0; r < kEdgeUnroll; ++r) {
-            u[r] = u_next[r];
-            // taken here, before the requests below are issued: loads return in order, and a wait
-            // for these entries placed after those requests would wait for them as well
-            asm volatile("" : "+v"(u[r]));
-        }
-        const uint64_t left = deg - e0;
-        const uint32_t cnt = left < kBatch ? (uint32_t)left : kBatch;
-        const bool row_ends = left <= kBatch;
-        const uint32_t t_now = t;
-        // ---- request the next step's entries before working on this one
-        if (row_ends) {
-            advance();
-            skip_empty_rows();
-        } else {
-            e0 += kBatch;
-        }
-        if (t < a.n_prev) request_entries(u_next);
-
-        // ---- entries that pass the bit test join the queue, in order.  Two copies of the code: a
-        // full step (the common case) tests nothing but the bit.
-        auto enqueue = [&](auto full_step) {
-            constexpr bool kFull = decltype(full_step)::value;
-#pragma unroll
-            for (int r = 0; r < kEdgeUnroll; ++r) {
-                if (!kFull && (uint32_t)r * 64u >= cnt) break;  // the same for the whole wavefront
-                const uint32_t bi = map_bit(u[r]);
-                bool pass = ((s_bits[bi >> 5] >> (bi & 31u)) & 1u) != 0u;
-                if (!kFull) pass = pass && (uint32_t)r * 64u + (uint32_t)lane < cnt;
-                const uint64_t votes = __ballot(pass);
-                const uint32_t ahead = __builtin_amdgcn_mbcnt_hi((uint32_t)(votes >> 32),
-                                                                 __builtin_amdgcn_mbcnt_lo((uint32_t)votes, 0u));
-                // no branch: a lane that does not pass writes to the queue's spare last place
-                queue[pass ? queued + ahead : kQueueCap - 1u] = u[r];
-                queued += (uint32_t)__popcll(votes);
+            if (it < n_items) {
+                const uint64_t key = s_trans[s_heads[it]];
+                const int32_t v = wave_uniform((int32_t)(uint32_t)(key >> 32));
+                off_a0 = g.off[v];
+                off_a1 = g.off[v + 1];
+                if constexpr (FILL) {
+                    const uint32_t slot = wave_uniform((uint32_t)key);
+                    rp_a0 = a.row_ptr[row0 + slot];
+                    rp_a1 = a.row_ptr[row0 + slot + 1];
+                }
             }
         };
-        if (cnt == kBatch) enqueue(std::true_type{});
-        else enqueue(std::false_type{});
-        wave_lds_order();
-
-        // ---- the table is probed by 64 queued entries at a time (by what is left when the row ends)
-        uint32_t head = 0;
-        while (queued - head >= 64u || (row_ends && head < queued)) {
-            const uint32_t n = queued - head < 64u ? queued - head : 64u;
-            const int32_t v = (uint32_t)lane < n ? queue[head + lane] : ND_NULL_VERTEX;
-            uint32_t c = 0, k = 0;
-            if (v >= 0) {
-                const uint32_t h = hash_vertex(v);
-                const uint32_t fp = fingerprint(h);
-                uint32_t pos = h >> a.hash_shift;
-                uint32_t en;
-                while ((en = table[pos]) != kEmpty) {  // ends: the table is never full
-                    if ((en >> 23) == fp && (int32_t)(s_sorted[en & 0x7FFu] >> 32) == v) {
-                        k = en & 0x7FFu;
-                        c = (en >> 11) & 0xFFFu;
-                        break;
-                    }
-                    pos = (pos + 1u) & mask;
-                }
-            }
+        bool no_edges = false;  // FILL: the counting pass found nothing for this item
+        auto adopt = [&]() {     // the item ahead becomes the item being requested
+            rs = wave_uniform((uint64_t)off_a0);
+            deg = wave_uniform((uint64_t)off_a1) - rs;
             if constexpr (FILL) {
-                // the lanes hold runs (k, c), most of them empty or one entry long: a lane writes
-                // its run entry by entry from the running sum of the lanes below it (the loop is
-                // the same in all lanes and ends with the longest run)
-                const uint32_t incl = wave_inclusive_scan(c, lane);
-                const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
-                const uint32_t ex = incl - c;
-                if (__ballot(c > 8u) == 0ull) {
-                    for (uint32_t i = 0; __ballot(i < c) != 0ull; ++i)
-                        if (i < c && wbase + ex + i < a.capacity)
-                            a.edge_slot[wbase + ex + i] = (int32_t)(uint32_t)s_sorted[k + i];
-                    wbase += total;
-                    head += n;
-                    continue;
-                }
-                // a vertex held by many slots: the entries are written in lane order, 64 at a
-                // time, each output position finding its lane by a search over the running sums
-                for (uint32_t base = 0; base < total; base += 64) {
-                    const uint32_t p = base + lane;
-                    uint32_t owner = 0;
+                no_edges = wave_uniform(rp_a1) == wave_uniform(rp_a0);
+                if (no_edges) deg = 0;
+            }
+            e0 = 0;
+            if (item < n_items) slots_of(item, &p0, &p1);
+            request_a(item + kStride);
+        };
+        // an item without entries to stream: its slots' counts are 0 (counting pass), nothing else
+        auto skip_empty_items = [&]() {
+            while (item < n_items && deg == 0) {
+                if constexpr (!FILL)
+                    for (uint32_t d = p0 + (uint32_t)lane; d < p1; d += 64u)
+                        a.counts[row0 + (uint32_t)s_trans[d]] = 0;
+                item += kStride;
+                adopt();
+            }
+        };
+        auto request_entries = [&](int32_t (&u)[kEdgeUnroll]) {
+            const int32_t* p = g.col + rs + e0;
+            const uint64_t left = deg - e0;
+            const uint32_t cnt = left < kBatch ? (uint32_t)left : kBatch;
+            if (cnt == kBatch) {  // a full step, the common case: nothing to test
 #pragma unroll
-                    for (uint32_t step = 32; step > 0; step >>= 1)
-                        if (__shfl(incl, (int)(owner + step - 1), 64) <= p) owner += step;
-                    owner &= 63u;
-                    const uint32_t ok = __shfl(k, (int)owner, 64);
-                    const uint32_t oex = __shfl(ex, (int)owner, 64);
-                    if (p < total && wbase + p < a.capacity)
-                        a.edge_slot[wbase + p] = (int32_t)(uint32_t)s_sorted[ok + (p - oex)];
+                for (int r = 0; r < kEdgeUnroll; ++r) u[r] = p[r * 64 + lane];
+                return;
+            }
+#pragma unroll
+            for (int r = 0; r < kEdgeUnroll; ++r) {
+                u[r] = ND_NULL_VERTEX;
+                // the test is the same in all lanes; inside the last 64 entries a lane past the end
+                // reads the last entry again instead of branching (and drops it when it looks at it:
+                // looking at it here would wait for each load in turn)
+                if ((uint32_t)r * 64u < cnt) {
+                    const uint32_t e = (uint32_t)r * 64u + (uint32_t)lane;
+                    u[r] = p[e < cnt ? e : cnt - 1u];
                 }
-                wbase += total;
+            }
+        };
+
+        request_a(item);
+        adopt();
+        skip_empty_items();
+        int32_t u_next[kEdgeUnroll];
+#pragma unroll
+        for (int r = 0; r < kEdgeUnroll; ++r) u_next[r] = 0;
+        if (item < n_items) request_entries(u_next);
+
+        uint32_t queued = 0;  // entries in the queue (the same in all lanes)
+        uint32_t count = 0;   // counting pass: my share of the item's edges
+        uint32_t done = 0;    // filling pass: edges of the item written so far (to each of its slots' rows)
+        uint32_t ofill = 0;   // filling pass: edges of the item waiting in obuf
+        while (item < n_items) {
+            // ---- the step whose entries have been requested
+            int32_t u[kEdgeUnroll];
+#pragma unroll
+            for (int r = 0; r < kEdgeUnroll; ++r) {
+                u[r] = u_next[r];
+                // taken here, before the requests below are issued: loads return in order, and a wait
+                // for these entries placed after those requests would wait for them as well
+                asm volatile("" : "+v"(u[r]));
+            }
+            const uint64_t left = deg - e0;
+            const uint32_t cnt = left < kBatch ? (uint32_t)left : kBatch;
+            const bool row_ends = left <= kBatch;
+            const uint32_t q0 = p0, q1 = p1;  // the slots of the item being worked on
+            // ---- request the next step's entries before working on this one
+            if (row_ends) {
+                item += kStride;
+                adopt();
+                skip_empty_items();
             } else {
-                count += c;
+                e0 += kBatch;
             }
-            head += n;
-        }
-        if (row_ends) {
-            if constexpr (!FILL) {
-                const uint32_t incl = wave_inclusive_scan(count, lane);
-                if (lane == 63) a.counts[row0 + t_now] = (int32_t)incl;
-                count = 0;
+            if (item < n_items) request_entries(u_next);
+
+            // ---- entries that pass the bit test join the queue, in order, 64 at a time; the table is
+            // probed by 64 queued entries at a time (by what is left when the item ends).  Two copies of
+            // the test: a full step (the common case) tests nothing but the bit.
+            // Filling pass: the edges found are collected in obuf, in order, and leave 64 at a time, one
+            // coalesced store per slot that holds the item's transit.
+            auto write_out = [&](uint32_t nf) {  // the first nf (at most 64) entries of obuf, to every row of the item
+                const int32_t val = (uint32_t)lane < nf ? obuf[lane] : 0;
+                for (uint32_t d0 = q0; d0 < q1; d0 += 64u) {
+                    // the rows of up to 64 slots at a time: their starts come by one load, a lane per slot
+                    const uint32_t nd = q1 - d0 < 64u ? q1 - d0 : 64u;
+                    int64_t my_row = 0;
+                    if ((uint32_t)lane < nd) my_row = a.row_ptr[row0 + (uint32_t)s_trans[d0 + lane]];
+                    for (uint32_t dd = 0; dd < nd; ++dd) {
+                        const int64_t wbase =
+                            (int64_t)(((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(my_row >> 32), dd) << 32) |
+                                      (uint32_t)__builtin_amdgcn_readlane((int)my_row, dd)) + done;
+                        if ((uint32_t)lane < nf && wbase + lane < a.capacity) a.edge_slot[wbase + lane] = val;
+                    }
+                }
+                done += nf;
+            };
+#pragma unroll
+            for (int r = 0; r < kEdgeUnroll; ++r) {
+                const bool in_step = cnt == kBatch || (uint32_t)r * 64u < cnt;  // the same for the whole wavefront
+                if (in_step) {
+                    const uint32_t bi = map_bit(u[r]);
+                    bool pass = ((s_bits[bi >> 5] >> (bi & 31u)) & 1u) != 0u;
+                    if (cnt != kBatch) pass = pass && (uint32_t)r * 64u + (uint32_t)lane < cnt;
+                    const uint64_t votes = __ballot(pass);
+                    const uint32_t ahead = __builtin_amdgcn_mbcnt_hi((uint32_t)(votes >> 32),
+                                                                     __builtin_amdgcn_mbcnt_lo((uint32_t)votes, 0u));
+                    // no branch: a lane that does not pass writes to the queue's spare last place
+                    queue[pass ? queued + ahead : kQueueCap - 1u] = u[r];
+                    queued += (uint32_t)__popcll(votes);
+                    wave_lds_order();
+                }
+                const bool last = row_ends && r == kEdgeUnroll - 1;
+                while (queued >= 64u || (last && queued > 0u)) {
+                // 64 queued entries (or, at the item's end, what is left)
+                const uint32_t n = queued < 64u ? queued : 64u;
+                const int32_t v = (uint32_t)lane < n ? queue[lane] : ND_NULL_VERTEX;
+                uint32_t c = 0, k = 0;
+                if (v >= 0) {
+                    const uint32_t h = hash_vertex(v);
+                    const uint32_t fp = fingerprint(h);
+                    uint32_t pos = h >> a.hash_shift;
+                    uint32_t en;
+                    while ((en = table[pos]) != kEmpty) {  // ends: the table is never full
+                        if ((en >> 23) == fp && (int32_t)(s_sorted[en & 0x7FFu] >> 32) == v) {
+                            k = en & 0x7FFu;
+                            c = (en >> 11) & 0xFFFu;
+                            break;
+                        }
+                        pos = (pos + 1u) & mask;
+                    }
+                }
+                if constexpr (FILL) {
+                    // the lanes hold runs (k, c); their entries go to obuf in lane order, 64 positions
+                    // at a time: a lane with a short run writes it itself, a long run (a vertex held by
+                    // many slots) is spread by a search over the running sums
+                    const uint32_t incl = wave_inclusive_scan(c, lane);
+                    const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+                    const uint32_t ex = incl - c;
+                    if (total <= 64u && __ballot(c > 8u) == 0ull) {
+                        for (uint32_t i = 0; __ballot(i < c) != 0ull; ++i)
+                            if (i < c) obuf[ofill + ex + i] = (int32_t)(uint32_t)s_sorted[k + i];
+                        ofill += total;
+                        wave_lds_order();
+                        if (ofill >= 64u) {
+                            write_out(64u);
+                            const int32_t moved = (uint32_t)lane < ofill - 64u ? obuf[64 + lane] : 0;
+                            wave_lds_order();
+                            if ((uint32_t)lane < ofill - 64u) obuf[lane] = moved;
+                            ofill -= 64u;
+                            wave_lds_order();
+                        }
+                    } else {
+                        for (uint32_t base = 0; base < total; base += 64u) {
+                            const uint32_t p = base + lane;
+                            uint32_t owner = 0;
+#pragma unroll
+                            for (uint32_t step = 32; step > 0; step >>= 1)
+                                if (__shfl(incl, (int)(owner + step - 1), 64) <= p) owner += step;
+                            owner &= 63u;
+                            const uint32_t ok = __shfl(k, (int)owner, 64);
+                            const uint32_t oex = __shfl(ex, (int)owner, 64);
+                            const uint32_t nb = total - base < 64u ? total - base : 64u;
+                            if (p < total) obuf[ofill + lane] = (int32_t)(uint32_t)s_sorted[ok + (p - oex)];
+                            ofill += nb;
+                            wave_lds_order();
+                            if (ofill >= 64u) {
+                                write_out(64u);
+                                const int32_t moved = (uint32_t)lane < ofill - 64u ? obuf[64 + lane] : 0;
+                                wave_lds_order();
+                                if ((uint32_t)lane < ofill - 64u) obuf[lane] = moved;
+                                ofill -= 64u;
+                                wave_lds_order();
+                            }
+                        }
+                    }
+                } else {
+                    count += c;
+                }
+                // what is left of the queue moves to the front
+                const uint32_t rest = queued - n;
+                const int32_t moved = (uint32_t)lane < rest ? queue[n + lane] : 0;
+                wave_lds_order();
+                if ((uint32_t)lane < rest) queue[lane] = moved;
+                queued = rest;
+                wave_lds_order();
+                }
+                if (last) {  // the item ends
+                    if constexpr (!FILL) {
+                        const uint32_t incl = wave_inclusive_scan(count, lane);
+                        const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+                        for (uint32_t d = q0 + (uint32_t)lane; d < q1; d += 64u)
+                            a.counts[row0 + (uint32_t)s_trans[d]] = (int32_t)total;
+                        count = 0;
+                    } else {
+                        if (ofill > 0u) write_out(ofill);
+                        ofill = 0;
+                        done = 0;
+                        wave_lds_order();
+                    }
+                }
             }
-            queued = 0;
-            wbase = wb;  // of the row the next step belongs to
-            wave_lds_order();
-        } else if (head > 0u) {  // fewer than 64 are left: they move to the front
-            const uint32_t rest = queued - head;
-            const int32_t moved = (uint32_t)lane < rest ? queue[head + lane] : 0;
-            wave_lds_order();
-            if ((uint32_t)lane < rest) queue[lane] = moved;
-            queued = rest;
-            wave_lds_order();
         }
+        __syncthreads();  // the chunk's sorted transits are replaced by the next chunk's
     }
     if (bad && a.status) atomicOr(a.status, 1u);
 }
@@ -452,7 +568,7 @@ inline EdgeArgs make_args(const int32_t* transits, int32_t n_prev, const int32_t
     a.m = (uint32_t)m;
     a.m2 = pow2_at_least((uint32_t)m);
     uint32_t lg = 0;
-    while ((1u << lg) < 4u * a.m2) ++lg;
+    while ((1u << lg) < 2u * a.m2) ++lg;
     a.hash_shift = 32u - lg;
     return a;
 }
