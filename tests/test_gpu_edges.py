@@ -31,7 +31,8 @@ _small64 = inputs.small_graph(scale=9, edges=9000, seed=17, int64_offsets=True)
 
 
 @pytest.mark.parametrize("n_prev,m,S", [(1, 1, 1), (64, 64, 7), (64, 2048, 5), (2048, 2048, 3), (100, 777, 9),
-                                        (3, 65, 300), (513, 1, 4)])
+                                        (3, 65, 300), (513, 1, 4),
+                                        (2049, 2048, 2), (4200, 64, 2)])   # more than one chunk of transit slots
 def test_edges_between_random_layers(n_prev, m, S):
     g = _small
     rng = np.random.default_rng(n_prev * 7919 + m)
