@@ -150,7 +150,7 @@ __global__ __launch_bounds__(kEdgeThreads) void edges_kernel(GraphView<OffT> g, 
     uint64_t* s_trans = (uint64_t*)(s_out + (kEdgeThreads / 64) * kOutCap);  // [kChunk] (transit << 32 | slot), sorted
     uint16_t* s_heads = (uint16_t*)(s_trans + kChunk);    // [kChunk] where each distinct transit starts in s_trans
     __shared__ uint32_t s_scan[kEdgeThreads / 64 + 1];
-    __shared__ uint32_t s_items[2];                       // distinct transits and live slots of the chunk
+    __shared__ uint32_t s_items[3];                       // distinct transits and live slots of the chunk; next item to hand out
     const uint32_t b = blockIdx.x;
     const uint32_t tid = threadIdx.x;
     const uint32_t mask = 2u * a.m2 - 1u;
@@ -250,6 +250,7 @@ __global__ __launch_bounds__(kEdgeThreads) void edges_kernel(GraphView<OffT> g, 
             if (tid == 0) {
                 s_items[0] = total & 0xFFFFu;
                 s_items[1] = total >> 16;
+                s_items[2] = 0;
             }
 #pragma unroll
             for (int e = 0; e < 2; ++e)
@@ -260,7 +261,15 @@ __global__ __launch_bounds__(kEdgeThreads) void edges_kernel(GraphView<OffT> g, 
         const uint32_t n_live = wave_uniform(s_items[1]);  // the live slots are the first n_live of s_trans
 
         // the item whose entries are being requested: positions [p0, p1) of s_trans hold its slots
-        uint32_t item = wave;
+        // the wavefronts take the items in order from a counter: lists differ in length by orders of
+        // magnitude, and a fixed share per wavefront leaves most of them waiting for the slowest
+        auto claim = [&]() -> uint32_t {
+            uint32_t i = 0;
+            if (lane == 0) i = atomicAdd(&s_items[2], 1u);
+            return wave_uniform(i);
+        };
+        uint32_t item = claim();
+        uint32_t item_next = claim();  // its offsets are requested while `item` is worked on
         uint32_t p0 = 0, p1 = 0;
         uint64_t rs = 0, deg = 0;   // where its adjacency list starts and how long it is (0: nothing to stream)
         uint64_t e0 = 0;            // the next entry of it to request
@@ -296,7 +305,7 @@ __global__ __launch_bounds__(kEdgeThreads) void edges_kernel(GraphView<OffT> g, 
             }
             e0 = 0;
             if (item < n_items) slots_of(item, &p0, &p1);
-            request_a(item + kStride);
+            request_a(item_next);
         };
         // an item without entries to stream: its slots' counts are 0 (counting pass), nothing else
         auto skip_empty_items = [&]() {
@@ -304,7 +313,8 @@ __global__ __launch_bounds__(kEdgeThreads) void edges_kernel(GraphView<OffT> g, 
                 if constexpr (!FILL)
                     for (uint32_t d = p0 + (uint32_t)lane; d < p1; d += 64u)
                         a.counts[row0 + (uint32_t)s_trans[d]] = 0;
-                item += kStride;
+                item = item_next;
+                item_next = claim();
                 adopt();
             }
         };
@@ -358,7 +368,8 @@ __global__ __launch_bounds__(kEdgeThreads) void edges_kernel(GraphView<OffT> g, 
             const uint32_t q0 = p0, q1 = p1;  // the slots of the item being worked on
             // ---- request the next step's entries before working on this one
             if (row_ends) {
-                item += kStride;
+                item = item_next;
+                item_next = claim();
                 adopt();
                 skip_empty_items();
             } else {
