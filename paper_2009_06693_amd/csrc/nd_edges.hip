@@ -64,6 +64,7 @@ struct EdgeArgs {
     int32_t* edge_slot;
     int64_t capacity;
     uint32_t* status;
+    int vertex_bits;          // bits of the largest vertex id
 };
 
 // Table entry: bits 0-10 first position of the vertex's run in the sorted list, bits 11-22 the
@@ -83,60 +84,78 @@ __device__ __forceinline__ void wave_lds_order() {
     __builtin_amdgcn_wave_barrier();
 }
 
-// Bitonic sorting network over the n2 (at most 2 * kEdgeThreads) keys of an LDS array, ascending;
-// every thread of the workgroup calls it, after a barrier that made the keys visible, and it ends
-// with one.  The keys live in registers, two per thread (keys t and t + kEdgeThreads; missing ones
-// count as the largest value): of the 66 compare-exchange steps of 2,048 keys, the 51 whose partner
-// is less than 64 keys away are lane exchanges inside the wavefront, one pairs a thread's own two
-// keys, and only 14 go through LDS and a workgroup barrier.  (With every step through LDS the sort
-// took 54 us per workgroup, more than streaming the adjacency lists of 64 transits.)
-__device__ __forceinline__ uint64_t exchange_step(uint64_t mine, uint64_t theirs, bool keep_min) {
-    const bool theirs_smaller = theirs < mine;
-    return (theirs_smaller == keep_min) ? theirs : mine;
-}
-__device__ __forceinline__ uint64_t lane_xor64(uint64_t x, int j) {
-    const uint32_t lo = (uint32_t)__shfl_xor((int)(uint32_t)x, j, 64);
-    const uint32_t hi = (uint32_t)__shfl_xor((int)(uint32_t)(x >> 32), j, 64);
-    return ((uint64_t)hi << 32) | lo;
-}
-__device__ __forceinline__ void bitonic_sort_lds(uint64_t* keys, uint32_t n2, uint32_t tid) {
+// Sorts the n2 (a power of two, at most 2 * kEdgeThreads) keys (vertex << 32 | slot) of an LDS array
+// by vertex; the slots arrive ascending and the sort is stable, so the keys end ascending.  Every
+// thread of the workgroup calls it, after a barrier that made the keys visible, and it ends with
+// one.  An LSD radix sort over the vertex's bits plus one (missing keys are all ones and must end
+// behind the largest vertex), 8 bits per pass: a wavefront owns 128 consecutive keys, ranks them
+// with one ballot per digit bit, the per-wavefront digit counts are scanned, and the keys, which
+// sit in registers meanwhile, go back to their places.  Three passes for 4 M vertices where a
+// bitonic network takes 66 compare-exchange steps (54 us per workgroup through LDS, 32 us in
+// registers with lane exchanges: more than streaming the adjacency lists of 64 transits).
+// hist: kEdgeThreads / 64 rows of 256 counters; digit_start: 256 entries; scan_tmp: for the scan.
+__device__ __forceinline__ void sort_keys_lds(uint64_t* keys, uint32_t n2, uint32_t tid, int vertex_bits,
+                                              uint32_t* hist, uint32_t* digit_start, uint32_t* scan_tmp) {
     constexpr uint32_t T = (uint32_t)kEdgeThreads;
     const bool two = n2 > T;  // the same for the whole workgroup
-    const uint32_t N = two ? 2u * T : T;
-    uint64_t k0 = tid < n2 ? keys[tid] : ~0ull;
-    uint64_t k1 = (two && tid + T < n2) ? keys[tid + T] : ~0ull;
-    __syncthreads();  // everybody has its keys: the array is free for the exchanges below
-    for (uint32_t k = 2; k <= N; k <<= 1) {
-        const bool asc0 = (tid & k) == 0, asc1 = ((tid + T) & k) == 0;
-        for (uint32_t j = k >> 1; j > 0; j >>= 1) {
-            if (j == T) {  // a thread's own two keys; tid < T <= k / 2, so this pair sorts ascending
-                if (k1 < k0) {
-                    const uint64_t t = k0;
-                    k0 = k1;
-                    k1 = t;
-                }
-                continue;
-            }
-            uint64_t p0, p1 = ~0ull;
-            if (j >= 64u) {
-                keys[tid] = k0;
-                if (two) keys[tid + T] = k1;
-                __syncthreads();
-                p0 = keys[tid ^ j];
-                if (two) p1 = keys[(tid ^ j) + T];
-                __syncthreads();
-            } else {
-                p0 = lane_xor64(k0, (int)j);
-                if (two) p1 = lane_xor64(k1, (int)j);
-            }
-            const bool lower = (tid & j) == 0;  // my key is the pair's first (also for key t + T: j < T)
-            k0 = exchange_step(k0, p0, lower == asc0);
-            if (two) k1 = exchange_step(k1, p1, lower == asc1);
+    const uint32_t wave = tid >> 6, lane = tid & 63u;
+    const uint32_t per_wave = two ? 128u : 64u;
+    const uint32_t at0 = wave * per_wave + lane, at1 = at0 + 64u;
+    uint32_t* my_hist = hist + wave * 256u;
+    const int total_bits = vertex_bits + 1;
+    const int passes = (total_bits + 7) / 8;
+    int shift = 0;
+    for (int pass = 0; pass < passes; ++pass) {
+        const int bits = total_bits / passes + (pass >= passes - total_bits % passes ? 1 : 0);
+        const uint32_t dmask = (1u << bits) - 1u;
+        const uint64_t k0 = at0 < n2 ? keys[at0] : ~0ull;
+        const uint64_t k1 = (two && at1 < n2) ? keys[at1] : ~0ull;
+        for (uint32_t i = lane; i < 256u; i += 64u) my_hist[i] = 0u;
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        const uint32_t d0 = ((uint32_t)(k0 >> 32) >> shift) & dmask;
+        const uint32_t d1 = ((uint32_t)(k1 >> 32) >> shift) & dmask;
+        uint32_t r0, r1 = 0;
+        {
+            const uint64_t peers = digit_peers(d0, ~0ull, bits);
+            const uint32_t below = __builtin_amdgcn_mbcnt_hi((uint32_t)(peers >> 32),
+                                                             __builtin_amdgcn_mbcnt_lo((uint32_t)peers, 0u));
+            const uint32_t old = my_hist[d0];  // read by all lanes before the lowest peer writes it
+            if (below == 0u) my_hist[d0] = old + (uint32_t)__popcll(peers);
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            r0 = old + below;
         }
+        if (two) {
+            const uint64_t peers = digit_peers(d1, ~0ull, bits);
+            const uint32_t below = __builtin_amdgcn_mbcnt_hi((uint32_t)(peers >> 32),
+                                                             __builtin_amdgcn_mbcnt_lo((uint32_t)peers, 0u));
+            const uint32_t old = my_hist[d1];
+            if (below == 0u) my_hist[d1] = old + (uint32_t)__popcll(peers);
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            r1 = old + below;
+        }
+        __syncthreads();
+        uint32_t cnt = 0;
+        if (tid < (1u << bits)) {  // per digit: exclusive scan over the wavefronts, in place
+#pragma unroll
+            for (uint32_t w = 0; w < T / 64u; ++w) {
+                const uint32_t t = hist[w * 256u + tid];
+                hist[w * 256u + tid] = cnt;
+                cnt += t;
+            }
+        }
+        uint32_t total;
+        const uint32_t ex = block_exclusive_scan<uint32_t, kEdgeThreads>(cnt, scan_tmp, &total);
+        if (tid < (1u << bits)) digit_start[tid] = ex;
+        __syncthreads();
+        // every key is in a register: the array can be overwritten
+        if (at0 < n2) keys[digit_start[d0] + my_hist[d0] + r0] = k0;
+        if (two && at1 < n2) keys[digit_start[d1] + my_hist[d1] + r1] = k1;
+        __syncthreads();
+        shift += bits;
     }
-    keys[tid] = k0;  // the array holds at least N entries
-    if (two) keys[tid + T] = k1;
-    __syncthreads();
 }
 
 template <typename OffT, bool FILL>
@@ -173,7 +192,7 @@ __global__ __launch_bounds__(kEdgeThreads) void edges_kernel(GraphView<OffT> g, 
     for (uint32_t i = tid; i < (uint32_t)kBitWords; i += kEdgeThreads) s_bits[i] = 0u;
     __syncthreads();
 
-    bitonic_sort_lds(s_sorted, a.m2, tid);
+    sort_keys_lds(s_sorted, a.m2, tid, a.vertex_bits, (uint32_t*)s_queue, (uint32_t*)s_heads, s_scan);
 
     // the first entry of every run of equal vertices puts the run into the table (the table has
     // twice as many places as there can be runs, so the probe loops end)
@@ -230,7 +249,7 @@ __global__ __launch_bounds__(kEdgeThreads) void edges_kernel(GraphView<OffT> g, 
             s_trans[i] = key;
         }
         __syncthreads();
-        bitonic_sort_lds(s_trans, n2, tid);
+        sort_keys_lds(s_trans, n2, tid, a.vertex_bits, (uint32_t*)s_queue, (uint32_t*)s_heads, s_scan);
         {   // where the distinct transits start (two positions per thread: n2 <= 2 * kEdgeThreads)
             bool head[2];
             uint32_t mine = 0, live = 0;
@@ -571,7 +590,8 @@ inline uint32_t pow2_at_least(uint32_t x) {
     return p;
 }
 
-inline EdgeArgs make_args(const int32_t* transits, int32_t n_prev, const int32_t* sampled, int32_t m) {
+inline EdgeArgs make_args(const Graph& gr, const int32_t* transits, int32_t n_prev, const int32_t* sampled,
+                          int32_t m) {
     EdgeArgs a{};
     a.transits = transits;
     a.sampled = sampled;
@@ -581,6 +601,8 @@ inline EdgeArgs make_args(const int32_t* transits, int32_t n_prev, const int32_t
     uint32_t lg = 0;
     while ((1u << lg) < 2u * a.m2) ++lg;
     a.hash_shift = 32u - lg;
+    a.vertex_bits = 1;
+    while (a.vertex_bits < 31 && (1ll << a.vertex_bits) < gr.V) ++a.vertex_bits;
     return a;
 }
 
@@ -617,7 +639,7 @@ int edges_count(const Graph& gr, const int32_t* transits, int32_t n_prev, const 
     const int64_t tiles = scan_tiles(rows);
     hipLaunchKernelGGL(edges_clear_status_kernel, dim3(1), dim3(1), 0, stream, status);
     if (num_samples > 0) {
-        EdgeArgs a = make_args(transits, n_prev, sampled, m);
+        EdgeArgs a = make_args(gr, transits, n_prev, sampled, m);
         a.counts = counts;
         a.status = status;
         if (gr.off64)
@@ -640,7 +662,7 @@ int edges_fill(const Graph& gr, const int32_t* transits, int32_t n_prev, const i
                int32_t m, int64_t num_samples, const int64_t* row_ptr, int32_t* edge_slot,
                int64_t capacity, hipStream_t stream) {
     if (num_samples == 0) return ND_OK;
-    EdgeArgs a = make_args(transits, n_prev, sampled, m);
+    EdgeArgs a = make_args(gr, transits, n_prev, sampled, m);
     a.row_ptr = row_ptr;
     a.edge_slot = edge_slot;
     a.capacity = capacity;
