@@ -7,24 +7,27 @@
 // The paper's kernel tests each new vertex against each transit.  Here one
 // workgroup per sample puts the sample's new vertices into an LDS hash table
 // once and then streams the adjacency lists of the sample's transits through
-// it: a wavefront reads 64 consecutive adjacency entries per iteration
-// (coalesced) and probes the table, so the cost is one LDS probe per adjacency
-// entry instead of a binary search per (transit, new vertex) pair.
+// it, 64 consecutive (coalesced) entries per wavefront load, so the cost is
+// per adjacency entry instead of a binary search per (transit, new vertex) pair.
 //
 // Output is one CSR over the rows (sample, transit slot).  A row lists the new
 // slots j whose vertex is a neighbour of the row's transit, ordered by (vertex
 // id, j) - the order a walk down the ascending adjacency list meets them - so
 // the result is unique.  To make that order cheap the sample's (vertex, slot)
-// pairs are sorted once in LDS (bitonic network); the hash table maps a vertex
-// to its run in the sorted list.  A table entry is one 32-bit word (fingerprint
-// of the vertex, start and length of the run) in a table four times the number
-// of slots; a fingerprint match is confirmed against the sorted list.
+// pairs are sorted once in LDS (a radix sort); the hash table maps a vertex to
+// its run in the sorted list.  A table entry is one 32-bit word (fingerprint of
+// the vertex, start and length of the run) in a table twice the number of
+// slots; a fingerprint match is confirmed against the sorted list.
 //
 // Nine adjacency entries in ten are of no sample vertex, and the kernel is bound by instruction
 // issue, not by the 4 bytes per entry it streams.  So an entry first tests one bit of a 65,536-bit
 // map of the sample's vertices (no loop, no divergence); the few that pass are packed, in order,
 // into a queue of the wavefront in LDS, and the table is probed by a full wavefront of queued
 // entries at a time.
+//
+// The sample's transit slots are sorted by vertex as well: a vertex that several slots hold (layer
+// samples hold well-connected vertices many times over) is streamed once, and what is found goes to
+// the row of each of those slots.  The wavefronts take the distinct transits from a counter.
 //
 // Two passes share the kernel: counting (row sizes, then a device-wide
 // exclusive scan into 64-bit row pointers) and filling.
