@@ -42,14 +42,12 @@ namespace nd {
 namespace {
 
 constexpr int kEdgeThreads = 1024;  // two workgroups (76 KB of LDS each) fill a CU's 32 wave slots
-constexpr int kEdgeUnroll = 4;      // adjacency loads in flight per lane and step
-constexpr uint32_t kBatch = 64 * kEdgeUnroll;  // adjacency entries a wavefront takes per step
 constexpr int kBitWords = 2048;     // the vertex map: 65,536 bits, indexed by the vertex id folded to 16 bits
 constexpr uint32_t kQueueCap = 64 + 64;        // fewer than 64 left over plus a quarter step's entries
 constexpr uint32_t kOutCap = 64 + 64;          // filling pass: edges of the current transit not yet written
 constexpr int kMaxSlots = 2048;  // new vertices per sample (ND_MAX_EDGE_SLOTS)
 constexpr int kChunk = 2048;     // transit slots of a sample that are sorted and de-duplicated together
-constexpr size_t kEdgeLdsBytes = (size_t)kMaxSlots * 8 + (size_t)2 * kMaxSlots * 4 + (size_t)kBitWords * 4 +
+constexpr size_t kEdgeLdsBytes = (size_t)kMaxSlots * 8 + (size_t)2 * kMaxSlots * 4 +
                                  (size_t)(kEdgeThreads / 64) * (kQueueCap + kOutCap) * 4 + (size_t)kChunk * 8 +
                                  (size_t)kChunk * 2;
 constexpr int kScanThreads = 256;
@@ -161,18 +159,29 @@ __device__ __forceinline__ void sort_keys_lds(uint64_t* keys, uint32_t n2, uint3
     }
 }
 
+// Two workgroups of 1,024 threads per compute unit are eight wavefronts per SIMD.  That takes at most
+// 64 vector registers and, on this register file (800 scalar registers per SIMD), at most 96 scalar
+// registers per wavefront: left to itself the compiler uses more scalar registers than that, which
+// silently halves the occupancy, so the bound is stated (the surplus goes to lanes of a vector register).
 template <typename OffT, bool FILL>
-__global__ __launch_bounds__(kEdgeThreads) void edges_kernel(GraphView<OffT> g, EdgeArgs a) {
+__global__ __launch_bounds__(kEdgeThreads) __attribute__((amdgpu_waves_per_eu(8, 8)))
+void edges_kernel(GraphView<OffT> g, EdgeArgs a) {
     extern __shared__ __align__(16) unsigned char s_dyn[];
     uint64_t* s_sorted = (uint64_t*)s_dyn;                // [kMaxSlots] (vertex << 32 | slot), ascending; ~0 = none
     uint32_t* table = (uint32_t*)(s_sorted + kMaxSlots);  // [2 * kMaxSlots] entries as described above
-    uint32_t* s_bits = table + 2 * kMaxSlots;             // [kBitWords] bit set: some sample vertex hashes here
-    int32_t* s_queue = (int32_t*)(s_bits + kBitWords);    // per wavefront: entries that passed the bit test
+    int32_t* s_queue = (int32_t*)(table + 2 * kMaxSlots);  // per wavefront: entries that passed the bit test
     int32_t* s_out = s_queue + (kEdgeThreads / 64) * kQueueCap;  // per wavefront: edges waiting to be written
     uint64_t* s_trans = (uint64_t*)(s_out + (kEdgeThreads / 64) * kOutCap);  // [kChunk] (transit << 32 | slot), sorted
     uint16_t* s_heads = (uint16_t*)(s_trans + kChunk);    // [kChunk] where each distinct transit starts in s_trans
+    // bit set: some sample vertex hashes here.  Declared statically so that its address is a constant
+    // of the instruction that reads it (one read per adjacency entry).
+    __shared__ uint32_t s_bits[kBitWords];
     __shared__ uint32_t s_scan[kEdgeThreads / 64 + 1];
     __shared__ uint32_t s_items[3];                       // distinct transits and live slots of the chunk; next item to hand out
+    // Adjacency loads in flight per lane and step: eight where the kernel then still fits 64 vector
+    // registers (two workgroups per compute unit), four in the filling pass over 64-bit offsets.
+    constexpr int kEdgeUnroll = (FILL && sizeof(OffT) == 8) ? 4 : 8;
+    constexpr uint32_t kBatch = 64 * kEdgeUnroll;  // adjacency entries a wavefront takes per step
     const uint32_t b = blockIdx.x;
     const uint32_t tid = threadIdx.x;
     const uint32_t mask = 2u * a.m2 - 1u;
@@ -215,7 +224,7 @@ __global__ __launch_bounds__(kEdgeThreads) void edges_kernel(GraphView<OffT> g, 
         uint32_t pos = h >> a.hash_shift;
         while (atomicCAS(&table[pos], kEmpty, entry) != kEmpty) pos = (pos + 1u) & mask;
         const uint32_t bi = map_bit(v);
-        atomicOr(&s_bits[bi >> 5], 1u << (bi & 31u));
+        atomicOr(&s_bits[bi >> 5], 0x80000000u >> (bi & 31u));  // counted from the top: the test is a shift and a sign
     }
     __syncthreads();
 
@@ -227,7 +236,6 @@ __global__ __launch_bounds__(kEdgeThreads) void edges_kernel(GraphView<OffT> g, 
     // registers.  The loop runs over steps of up to kBatch entries of a list; the entries of the next
     // step (the same item's or the next item's) and the offsets of the item after are requested
     // before the current step is worked on.
-    constexpr uint32_t kStride = kEdgeThreads / 64;
     const int lane = lane_id();
     const uint32_t wave = wave_uniform((uint32_t)wave_id());
     int32_t* queue = s_queue + wave * kQueueCap;
@@ -293,8 +301,9 @@ __global__ __launch_bounds__(kEdgeThreads) void edges_kernel(GraphView<OffT> g, 
         uint32_t item = claim();
         uint32_t item_next = claim();  // its offsets are requested while `item` is worked on
         uint32_t p0 = 0, p1 = 0;
-        uint64_t rs = 0, deg = 0;   // where its adjacency list starts and how long it is (0: nothing to stream)
-        uint64_t e0 = 0;            // the next entry of it to request
+        uint64_t rs = 0;            // where its adjacency list starts
+        uint32_t deg = 0;           // how long it is (0: nothing to stream); a list has fewer than 2^31 entries
+        uint32_t e0 = 0;            // the next entry of it to request
         // one item ahead: offsets (FILL: row pointers of its first slot) requested
         OffT off_a0 = 0, off_a1 = 0;
         int64_t rp_a0 = 0, rp_a1 = 0;
@@ -320,7 +329,7 @@ __global__ __launch_bounds__(kEdgeThreads) void edges_kernel(GraphView<OffT> g, 
         bool no_edges = false;  // FILL: the counting pass found nothing for this item
         auto adopt = [&]() {     // the item ahead becomes the item being requested
             rs = wave_uniform((uint64_t)off_a0);
-            deg = wave_uniform((uint64_t)off_a1) - rs;
+            deg = (uint32_t)(wave_uniform((uint64_t)off_a1) - rs);
             if constexpr (FILL) {
                 no_edges = wave_uniform(rp_a1) == wave_uniform(rp_a0);
                 if (no_edges) deg = 0;
@@ -342,8 +351,8 @@ __global__ __launch_bounds__(kEdgeThreads) void edges_kernel(GraphView<OffT> g, 
         };
         auto request_entries = [&](int32_t (&u)[kEdgeUnroll]) {
             const int32_t* p = g.col + rs + e0;
-            const uint64_t left = deg - e0;
-            const uint32_t cnt = left < kBatch ? (uint32_t)left : kBatch;
+            const uint32_t left = deg - e0;
+            const uint32_t cnt = left < kBatch ? left : kBatch;
             if (cnt == kBatch) {  // a full step, the common case: nothing to test
 #pragma unroll
                 for (int r = 0; r < kEdgeUnroll; ++r) u[r] = p[r * 64 + lane];
@@ -384,8 +393,8 @@ __global__ __launch_bounds__(kEdgeThreads) void edges_kernel(GraphView<OffT> g, 
                 // for these entries placed after those requests would wait for them as well
                 asm volatile("" : "+v"(u[r]));
             }
-            const uint64_t left = deg - e0;
-            const uint32_t cnt = left < kBatch ? (uint32_t)left : kBatch;
+            const uint32_t left = deg - e0;
+            const uint32_t cnt = left < kBatch ? left : kBatch;
             const bool row_ends = left <= kBatch;
             const uint32_t q0 = p0, q1 = p1;  // the slots of the item being worked on
             // ---- request the next step's entries before working on this one
@@ -400,8 +409,7 @@ __global__ __launch_bounds__(kEdgeThreads) void edges_kernel(GraphView<OffT> g, 
             if (item < n_items) request_entries(u_next);
 
             // ---- entries that pass the bit test join the queue, in order, 64 at a time; the table is
-            // probed by 64 queued entries at a time (by what is left when the item ends).  Two copies of
-            // the test: a full step (the common case) tests nothing but the bit.
+            // probed by 64 queued entries at a time (by what is left when the item ends).
             // Filling pass: the edges found are collected in obuf, in order, and leave 64 at a time, one
             // coalesced store per slot that holds the item's transit.
             auto write_out = [&](uint32_t nf) {  // the first nf (at most 64) entries of obuf, to every row of the item
@@ -425,13 +433,16 @@ __global__ __launch_bounds__(kEdgeThreads) void edges_kernel(GraphView<OffT> g, 
                 const bool in_step = cnt == kBatch || (uint32_t)r * 64u < cnt;  // the same for the whole wavefront
                 if (in_step) {
                     const uint32_t bi = map_bit(u[r]);
-                    bool pass = ((s_bits[bi >> 5] >> (bi & 31u)) & 1u) != 0u;
-                    if (cnt != kBatch) pass = pass && (uint32_t)r * 64u + (uint32_t)lane < cnt;
-                    const uint64_t votes = __ballot(pass);
-                    const uint32_t ahead = __builtin_amdgcn_mbcnt_hi((uint32_t)(votes >> 32),
-                                                                     __builtin_amdgcn_mbcnt_lo((uint32_t)votes, 0u));
+                    const bool pass = (int32_t)(s_bits[bi >> 5] << (bi & 31u)) < 0;
+                    // The lanes past the list's end (its last step only) are struck from the votes, a
+                    // scalar operation, and not from `pass`: such a lane that passes writes to the place
+                    // after the last live entry (at most the spare one), which nothing reads.
+                    const uint32_t live = cnt - (uint32_t)r * 64u;
+                    const uint64_t votes = __ballot(pass) & (live >= 64u ? ~0ull : (1ull << live) - 1ull);
+                    const uint32_t at = __builtin_amdgcn_mbcnt_hi((uint32_t)(votes >> 32),
+                                                                  __builtin_amdgcn_mbcnt_lo((uint32_t)votes, queued));
                     // no branch: a lane that does not pass writes to the queue's spare last place
-                    queue[pass ? queued + ahead : kQueueCap - 1u] = u[r];
+                    queue[pass ? at : kQueueCap - 1u] = u[r];
                     queued += (uint32_t)__popcll(votes);
                     wave_lds_order();
                 }

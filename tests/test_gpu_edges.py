@@ -92,6 +92,25 @@ def test_a_vertex_held_by_many_slots_gives_one_edge_per_slot(copies):
     assert ptr[1] - ptr[0] >= copies
 
 
+@pytest.mark.parametrize("int64_offsets", [False, True])
+def test_adjacency_lists_that_end_at_and_around_the_kernels_step_sizes(int64_offsets):
+    """A wavefront streams a list in steps of 256 or 512 entries, 64 at a time: lists one short of,
+    equal to and one past the multiples, with the vertices looked for at their very ends."""
+    lengths = [1, 63, 64, 65, 255, 256, 257, 511, 512, 513, 767, 768, 1023, 1024, 1025, 1536, 2047, 2048, 2049, 4097]
+    V = 5000
+    rng = np.random.default_rng(77)
+    edges = []
+    for u, n in enumerate(lengths):
+        edges += [(u, int(v)) for v in np.sort(rng.choice(V, n, replace=False))]
+    g = inputs.from_edges(V, edges, int64_offsets=int64_offsets)
+    transits = np.array([np.arange(len(lengths)), np.arange(len(lengths))[::-1]], dtype=np.int32)
+    ends = [int(g.col_indices[g.row_offsets[u + 1] - 1]) for u in range(len(lengths))]   # the last entry of each list
+    firsts = [int(g.col_indices[g.row_offsets[u]]) for u in range(len(lengths))]
+    sampled = np.array([ends + firsts, rng.integers(0, V, 2 * len(lengths)).tolist()], dtype=np.int32)
+    ptr = _compare(g, transits, sampled)
+    assert ptr[len(lengths)] >= 2 * len(lengths) - 1     # every list holds its own first and last entry
+
+
 def test_empty_and_error_cases():
     g = _small
     dg, _ = device_graph(g)
