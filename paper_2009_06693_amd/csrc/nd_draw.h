@@ -61,7 +61,10 @@ __device__ __forceinline__ uint32_t n2v_bias(const GraphView<OffT>& g, const Dra
                                              uint64_t rs_t, uint32_t deg_t, int32_t u) {
     if (!a.has_prev) return kOneQ16;
     if (u == t) return a.b_ret;
-    return row_contains(g, rs_t, deg_t, u) ? a.b_com : a.b_far;
+    // values, not a choice between two members: the latter is a choice between two addresses and
+    // keeps the whole structure in memory
+    const uint32_t b_com = a.b_com, b_far = a.b_far;
+    return row_contains(g, rs_t, deg_t, u) ? b_com : b_far;
 }
 
 // t: the transit of the previous step (read only when a.has_prev).
@@ -80,8 +83,9 @@ __device__ __forceinline__ int32_t draw_node2vec(const GraphView<OffT>& g, const
         rs_t = (uint64_t)g.off[t];
         deg_t = row_length(g, t, rs_t);
     }
-    const uint32_t b_lo = a.b_com < a.b_far ? a.b_com : a.b_far;
-    const uint32_t b_hi = a.b_com < a.b_far ? a.b_far : a.b_com;
+    const uint32_t b_com = a.b_com, b_far = a.b_far;  // values: see n2v_bias
+    const uint32_t b_lo = b_com < b_far ? b_com : b_far;
+    const uint32_t b_hi = b_com < b_far ? b_far : b_com;
     for (int32_t att = 0; att < a.max_attempts; ++att) {
         const Rand4 r = draw4(a.seed, sid, 0u, a.step, (uint32_t)att);
         const uint32_t e = mulhi32(r.r0, deg);
@@ -95,7 +99,7 @@ __device__ __forceinline__ int32_t draw_node2vec(const GraphView<OffT>& g, const
         } else if (y < w * b_lo) {
             return u;
         } else if (y < w * b_hi) {
-            const uint32_t bias = row_contains(g, rs_t, deg_t, u) ? a.b_com : a.b_far;
+            const uint32_t bias = row_contains(g, rs_t, deg_t, u) ? b_com : b_far;
             if (y < w * bias) return u;
         }
     }

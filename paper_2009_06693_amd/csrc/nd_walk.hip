@@ -57,12 +57,27 @@ struct WalkArgs {
 };
 
 // One draw, out of line where the inlined code is long (the rejection loop of node2vec), so that
-// the unrolled per-slot loops below stay small.
-template <int DRAW, typename OffT>
-__device__ __noinline__ int32_t draw_n2v_call(const GraphView<OffT>& g, const DrawArgs& d, int32_t v,
-                                              uint64_t rs, uint32_t deg, uint32_t sid, int32_t t_prev,
-                                              const int32_t* adj) {
-    return draw_node2vec(g, d, v, deg, sid, t_prev, adj, d.use_weights ? g.wq + rs : nullptr);
+// the unrolled per-slot loops below stay small.  What it needs travels by value, in registers: a
+// structure handed over by reference has to live in scratch memory, and then for the whole kernel,
+// so that every other use of the graph's pointers would go through scratch as well.
+template <typename OffT>
+__device__ __noinline__ int32_t draw_n2v_call(const OffT* off, const int32_t* col, const uint32_t* wq_row,
+                                              const uint32_t* maxwq, uint64_t seed, uint32_t step,
+                                              uint32_t b_ret, uint32_t b_com, uint32_t b_far, uint32_t b_max,
+                                              int32_t max_attempts, int32_t has_prev, int32_t v, uint32_t deg,
+                                              uint32_t sid, int32_t t_prev, const int32_t* adj) {
+    const GraphView<OffT> g{off, col, nullptr, nullptr, maxwq, 0};
+    DrawArgs d;  // only the fields the draw reads are set
+    d.seed = seed;
+    d.step = step;
+    d.b_ret = b_ret;
+    d.b_com = b_com;
+    d.b_far = b_far;
+    d.b_max = b_max;
+    d.max_attempts = max_attempts;
+    d.has_prev = has_prev;
+    d.use_weights = wq_row != nullptr;
+    return draw_node2vec(g, d, v, deg, sid, t_prev, adj, wq_row);
 }
 
 template <int DRAW, typename OffT>
@@ -72,7 +87,8 @@ __device__ __forceinline__ int32_t draw_one(const GraphView<OffT>& g, const Draw
     if (deg == 0) return ND_NULL_VERTEX;
     if (DRAW == kDrawUniform) return draw_uniform(d, deg, sid, 0u, adj);
     if (DRAW == kDrawWeighted) return draw_weighted(d, deg, sid, 0u, adj, g.cumq + rs);
-    return draw_n2v_call<DRAW, OffT>(g, d, v, rs, deg, sid, t_prev, adj);
+    return draw_n2v_call<OffT>(g.off, g.col, d.use_weights ? g.wq + rs : nullptr, g.maxwq, d.seed, d.step, d.b_ret,
+                               d.b_com, d.b_far, d.b_max, d.max_attempts, d.has_prev, v, deg, sid, t_prev, adj);
 }
 
 // Bucket of the per-window transit table: [63:48] tag of the step that wrote it, [47:32] number
