@@ -19,8 +19,8 @@
 // the vertex, start and length of the run) in a table twice the number of
 // slots; a fingerprint match is confirmed against the sorted list.
 //
-// Nine adjacency entries in ten are of no sample vertex, and the kernel is bound by instruction
-// issue, not by the 4 bytes per entry it streams.  So an entry first tests one bit of a 65,536-bit
+// Nine adjacency entries in ten are of no sample vertex, and the kernel is bound as much by
+// instruction issue as by the 4 bytes per entry it streams.  So an entry first tests one bit of a 65,536-bit
 // map of the sample's vertices (no loop, no divergence); the few that pass are packed, in order,
 // into a queue of the wavefront in LDS, and the table is probed by a full wavefront of queued
 // entries at a time.
@@ -41,7 +41,7 @@ namespace nd {
 
 namespace {
 
-constexpr int kEdgeThreads = 1024;  // two workgroups (76 KB of LDS each) fill a CU's 32 wave slots
+constexpr int kEdgeThreads = 1024;  // two workgroups (78 KB of LDS each) fill a CU's 32 wave slots
 constexpr int kBitWords = 2048;     // the vertex map: 65,536 bits, indexed by the vertex id folded to 16 bits
 constexpr uint32_t kQueueCap = 64 + 64;        // fewer than 64 left over plus a quarter step's entries
 constexpr uint32_t kOutCap = 64 + 64;          // filling pass: edges of the current transit not yet written
