@@ -207,6 +207,7 @@ def run_workload(name, args, B, inputs, torch, np, cpu_baseline):
     roots = torch.as_tensor(roots_np, device="cuda:0")
     mode = B.ND_MODE_TRANSIT_PARALLEL if args.mode == "tp" else B.ND_MODE_SAMPLE_PARALLEL
     p = B.nd_params_init(mode=mode, sched_sub_max=args.sub_max, sched_wg_max=args.wg_max,
+                         lds_stage_policy=args.lds_policy,
                          sched_group_bits=args.group_bits, sched_force_class=args.force_class,
                          sched_window=args.window, **pkw)
     s = B.Sampler(dg, app, p, int(roots.numel()))
@@ -398,6 +399,8 @@ def main():
                     help="0: exact transit grouping (default); b: group by the top b bits of the vertex id only")
     ap.add_argument("--window", type=int, default=0,
                     help="walks: 0 windows of samples in LDS (default), -1 GPU-wide grouping, 1024 / 2048 window size")
+    ap.add_argument("--lds-policy", type=int, default=0, choices=[0, 1, 2],
+                    help="ablation: 0 stage adjacency lists in LDS where it pays (default), 1 never, 2 whenever they fit")
     ap.add_argument("--force-class", type=int, default=-1,
                     help="ablation: -1 balanced (default), 0/1/2 every transit sub-wavefront/workgroup/grid")
     args = ap.parse_args()
