@@ -137,7 +137,19 @@ def bench_layer_edges(args, B, inputs, torch, np):
                    "edges_per_step": edges, "adjacency_entries_of_all_transit_slots": streamed,
                    "adjacency_entries_streamed_per_pass": distinct},
         "phase_ms_per_step": {"sample": round(t_sample / k, 4), "edges_count": round(t_count / k, 4),
-                              "edges_fill": round(t_fill / k, 4)}}))
+                              "edges_fill": round(t_fill / k, 4)},
+        # the two counting passes of a call (edges_kernel + the row-pointer scan): 4 bytes per streamed
+        # adjacency entry + 4 per transit slot and per new vertex read + 4 per transit slot written,
+        # over their time between HIP events on the launch stream
+        "roofline": _edges_roofline(distinct, shapes, nb, t_count / k)}))
+
+
+def _edges_roofline(distinct, shapes, nb, count_ms):
+    algorithmic = sum(4 * distinct[i] + nb * (8 * shapes[i][1] + 4 * shapes[i + 1][1]) for i in range(2))
+    achieved = algorithmic / (count_ms * 1e-3) / 1e9
+    return {"kernel": "edges_kernel<counting pass>", "bound": "hbm", "achieved": round(achieved, 1), "peak": 8000.0,
+            "unit": "GB/s", "frac": round(achieved / 8000.0, 4), "traffic": None,
+            "algorithmic_bytes_per_call": algorithmic, "passes_per_call": 2}
 
 
 def measure_copy_gbps(torch, steps=5):
